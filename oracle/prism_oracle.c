@@ -6,7 +6,7 @@
  * leg can compare the GPU kernels against a slow, plain definition.  It
  * shares no code, header, table or helper with the GPU library.
  *
- * What it defines (paper Sec. 2.2: prefill "builds missing KV states", and KV
+ * What it defines (paper Sec. 2.2: prefill computes the KV states that are not yet cached, and KV
  * states may be reused only along an exact token prefix, Eq. 3; the effective
  * prefill work is the uncached remainder, Eq. 4):
  *

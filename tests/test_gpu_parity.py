@@ -1,0 +1,177 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_08581_amd import binding as B
+from paper_2605_08581_amd import workload as W
+
+from gpu_util import check_close, full_parity, run_hip, widen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    B.load()
+
+
+def test_tiny_config_all_rows(oracle_lib):
+    full_parity(oracle_lib, W.make_config(0))
+
+
+@pytest.mark.parametrize("tile_rows", [64, 128, 256])
+@pytest.mark.parametrize("geom", [W.Geometry(4, 4, 64), W.Geometry(8, 2, 128), W.Geometry(6, 6, 128),
+                                   W.Geometry(8, 1, 64)], ids=["mha64", "gqa4x128", "mha128", "mqa8x64"])
+def test_ragged_lengths_all_rows(oracle_lib, geom, tile_rows):
+    """Prefixes and suffixes that end inside pages and tiles, an empty request,
+    a request with no cached prefix, and a single-token one."""
+    prefix = [0, 16, 37, 200, 64, 129, 0]
+    suffix = [70, 0, 19, 33, 130, 65, 1]
+    b = W.make_custom_batch("ragged", geom, prefix, suffix, seed=5, share_groups=[-1, 0, -1, 0, 0, -1, -1])
+    full_parity(oracle_lib, b, tile_rows=tile_rows)
+
+
+@pytest.mark.parametrize("split_kv", [2, 3, 7])
+def test_split_kv_matches_oracle(oracle_lib, split_kv):
+    b = W.make_custom_batch("split", W.Geometry(8, 2, 128), [500, 0, 1000, 77], [40, 300, 7, 150], seed=6)
+    info = full_parity(oracle_lib, b, split_kv=split_kv)
+    assert info.num_reduce_groups > 0
+
+
+def test_split_and_unsplit_agree():
+    b = W.make_custom_batch("split", W.Geometry(4, 4, 128), [900, 130], [100, 260], seed=7)
+    t = W.make_tensors(b, "cuda")
+    a, _ = run_hip(b, {k: v.clone() for k, v in t.items()}, split_kv=1)
+    c, info = run_hip(b, {k: v.clone() for k, v in t.items()}, split_kv=4)
+    assert info.num_split_items > 0
+    # both are bf16 roundings of fp32 results that differ only in summation
+    # order: at most one bf16 ulp (2^-7 relative at the top binade) apart
+    dmax = float((a.double() - c.double()).abs().max())
+    amax = float(a.double().abs().max())
+    assert dmax <= 2.0 ** -7 * amax, (dmax, amax)
+
+
+@pytest.mark.parametrize("scale,name", [(1.0, "unit"), (4.0, "sharp")])
+def test_unscaled_and_sharp_inputs(oracle_lib, scale, name):
+    """q,k,v ~ N(0,1) (logits of order 1, outputs of order 0.1-1, so the
+    absolute tolerance bites) and q,k ~ 4 N(0,1) (logit std 16: the max
+    subtraction matters)."""
+    geom = W.Geometry(4, 2, 128)
+    b = W.make_custom_batch(name, geom, [96, 0, 333], [100, 257, 31], seed=8, value_scale=1.0)
+
+    def mutate(t):
+        for k in ("q", "k_suffix", "k_pool"):
+            t[k].mul_(scale)
+    full_parity(oracle_lib, b, mutate=mutate)
+
+
+def test_slots_past_the_sequence_are_ignored(oracle_lib):
+    """The last page's unused slots (and unrelated pages) hold NaN/Inf bit
+    patterns; results must not change."""
+    geom = W.Geometry(4, 4, 128)
+    b = W.make_custom_batch("nan", geom, [32, 0], [21, 70], seed=9)
+
+    def mutate(t):
+        for r in range(b.batch):
+            T = int(b.prefix_len[r] + b.suffix_len[r])
+            pg = int(b.block_table[r, (T - 1) // 16])
+            if T % 16:
+                t["k_pool"][pg, :, T % 16:, :] = float("nan")
+                t["v_pool"][pg, :, T % 16:, :] = float("inf")
+    full_parity(oracle_lib, b, mutate=mutate)
+
+
+def test_page_permutation_invariance():
+    geom = W.Geometry(8, 2, 128)
+    b = W.make_custom_batch("perm", geom, [128, 64], [50, 90], seed=10, permute_pages=False)
+    t = W.make_tensors(b, "cuda")
+    ref, _ = run_hip(b, {k: v.clone() for k, v in t.items()})
+    perm = np.random.default_rng(3).permutation(b.num_pages)
+    inv = torch.from_numpy(np.argsort(perm)).cuda()
+    b2 = W.Batch(**{**b.__dict__, "block_table": perm[b.block_table].astype(np.int32)})
+    t2 = {k: v.clone() for k, v in t.items()}
+    t2["k_pool"], t2["v_pool"] = t["k_pool"][inv].contiguous(), t["v_pool"][inv].contiguous()
+    got, _ = run_hip(b2, t2)
+    assert torch.equal(got, ref)
+
+
+def test_append_entry_point_alone_is_bit_exact(oracle_lib):
+    b = W.make_custom_batch("append", W.Geometry(40, 40, 128), [16, 5, 0, 48], [33, 12, 100, 1], seed=11,
+                            share_groups=[0, -1, -1, 0])
+    t = W.make_tensors(b, "cuda")
+    host = {k: W.bf16_bits(v) for k, v in t.items()}
+    sh = B.shape_of(b)
+    plan = B.Plan(sh, b.prefix_len, b.suffix_len)
+    bt = torch.from_numpy(b.block_table).cuda()
+    plan.prism_kv_append(t["k_suffix"], t["v_suffix"], t["k_pool"], t["v_pool"], bt)
+    torch.cuda.synchronize()
+    kp, vp = oracle_lib.kv_append(host["k_suffix"], host["v_suffix"], host["k_pool"], host["v_pool"],
+                                  b.block_table, b.prefix_len, b.suffix_len)
+    assert np.array_equal(W.bf16_bits(t["k_pool"]), kp) and np.array_equal(W.bf16_bits(t["v_pool"]), vp)
+
+
+def test_separate_entry_points_match_fused_call(oracle_lib):
+    b = W.make_custom_batch("sep", W.Geometry(8, 2, 128), [64, 0], [40, 129], seed=12)
+    full_parity(oracle_lib, b, entry="separate")
+
+
+def test_workspace_errors():
+    b = W.make_custom_batch("ws", W.Geometry(4, 4, 128), [900], [100], seed=13)
+    t = W.make_tensors(b, "cuda")
+    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, split_kv=4)
+    need = plan.prism_plan_workspace_bytes()
+    assert need > 0
+    bt = torch.from_numpy(b.block_table).cuda()
+    out = torch.empty_like(t["q"])
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.PrismError) as e:
+        plan.prism_prefix_attention(t["q"], t["k_pool"], t["v_pool"], bt, out, small)
+    assert e.value.code == B.ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(B.PrismError) as e:
+        plan.prism_prefix_attention(t["q"], t["k_pool"], t["v_pool"], bt, out, None)
+    assert e.value.code == B.ERR_INVALID_ARG
+    plan.close()
+
+
+def _sampled_parity(oracle_lib, b, n_rows, **opts):
+    """Full-size check: append bit-exact on every written row (read back through
+    the table) and untouched elsewhere; attention on sampled rows."""
+    t = W.make_tensors(b, "cuda")
+    k0, v0 = t["k_pool"].clone(), t["v_pool"].clone()
+    out, info = run_hip(b, t, **opts)
+    # append: compare against a torch index_put built from the table (integer work)
+    offs = b.suffix_offsets
+    req = np.repeat(np.arange(b.batch), b.suffix_len)
+    pos = np.concatenate([np.arange(int(b.prefix_len[r]), int(b.prefix_len[r] + b.suffix_len[r]))
+                          for r in range(b.batch)]) if b.total_suffix else np.zeros(0, np.int64)
+    page = torch.from_numpy(b.block_table[req, pos // 16].astype(np.int64)).cuda()
+    slot = torch.from_numpy((pos % 16).astype(np.int64)).cuda()
+    assert torch.equal(t["k_pool"][page, :, slot, :], t["k_suffix"])
+    assert torch.equal(t["v_pool"][page, :, slot, :], t["v_suffix"])
+    keep = torch.ones(b.num_pages, 16, dtype=torch.bool, device="cuda")
+    keep[page, slot] = False
+    assert torch.equal(t["k_pool"].transpose(1, 2)[keep], k0.transpose(1, 2)[keep])
+    assert torch.equal(t["v_pool"].transpose(1, 2)[keep], v0.transpose(1, 2)[keep])
+    del k0, v0
+    rows = W.sample_rows(b, n_rows, seed=1)
+    ref = oracle_lib.attention_rows(W.bf16_bits(t["q"]), W.bf16_bits(t["k_pool"]), W.bf16_bits(t["v_pool"]),
+                                    b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale, rows)
+    got = widen(W.bf16_bits(out[torch.from_numpy(offs[rows[:, 0]] + rows[:, 1]).cuda(),
+                                torch.from_numpy(rows[:, 2].astype(np.int64)).cuda()]))
+    check_close(got, ref, b.name)
+    assert torch.isfinite(out.float()).all()
+    return info
+
+
+@pytest.mark.parametrize("index", [1, 2, 4])
+def test_full_size_configs_sampled_rows(oracle_lib, index):
+    """The benchmark configurations at full size with the default plan (the
+    launch configuration the benchmark times)."""
+    _sampled_parity(oracle_lib, W.make_config(index), 1500)
+
+
+@pytest.mark.parametrize("hit", [0.0, 0.5, 0.9])
+def test_hit_rate_sweep_sampled_rows(oracle_lib, hit):
+    _sampled_parity(oracle_lib, W.make_hit_rate_batch(hit, batch=8), 600)
