@@ -65,6 +65,13 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2605_08581_amd.build` "
                            "(there is no CPU or PyTorch fallback)")
+    # PyTorch supplies the device memory and streams, so the library must use
+    # the HIP runtime PyTorch ships (same SONAME): make sure that copy is the
+    # one already in the process before libprism.so resolves its dependency.
+    import torch
+    rt = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if os.path.exists(rt):
+        ctypes.CDLL(rt, mode=ctypes.RTLD_GLOBAL)
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
     lib.prism_version.restype = ctypes.c_int
