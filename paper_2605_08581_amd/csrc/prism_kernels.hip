@@ -66,7 +66,10 @@ int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_po
 //
 // A workgroup of NW waves owns NW*32*RB packed query rows of one (request, kv
 // head) and walks the key range in tiles of 64 keys (four 16-token pages).
-// Each tile's K and V rows are staged in LDS once and used by all waves.
+// Each tile's K and V rows are copied from the paged pool straight into LDS
+// (global_load_lds, 16 bytes per lane, no staging registers) into one of two
+// buffers, so the copy of tile t+1 overlaps the math of tile t and there is
+// one workgroup barrier per tile.
 //
 // Per wave the products are taken transposed so that no value ever has to move
 // between lanes except one exchange for the row maximum:
@@ -80,6 +83,14 @@ int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_po
 //
 // LDS rows are d bf16 wide, 16-byte chunks XOR-swizzled by the key index so
 // that both the row reads (K) and the transposing reads (V) spread over banks.
+// A direct-to-LDS load writes lane l's 16 bytes at (wave-uniform base) + 16*l,
+// so the swizzle is applied on the global side: lane l fetches the chunk that
+// belongs in the slot it will fill.
+//
+// The running maximum is only raised when some row's tile maximum exceeds it
+// by more than 2^8 in the exponent domain: probabilities then stay below 256,
+// the final division by the row sum cancels the offset exactly, and the
+// accumulator rescale is skipped on almost every tile.
 // --------------------------------------------------------------------------
 
 template <int D>
@@ -95,8 +106,10 @@ __device__ __forceinline__ int lds_off(int key, int chunk) {   // byte offset of
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int D, int RB, int NW>
-__global__ __launch_bounds__(NW * 64) void prefill_attn_kernel(
+constexpr float kRescaleThreshold = 8.0f;   // log2 units
+
+template <int D, int RB, int NW, int WPE>
+__global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k_pool,
     const __bf16 *__restrict__ v_pool, const int32_t *__restrict__ block_table,
     __bf16 *__restrict__ out, float *__restrict__ partials, const AttnItem *__restrict__ items,
@@ -105,20 +118,21 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_kernel(
   constexpr int NT = NW * 64;
   constexpr int BM = NW * 32 * RB;
   constexpr int CPR = D / 8;                     // 16-byte chunks per key row
-  constexpr int TILE_CHUNKS = BN * CPR;
-  constexpr int LOADS = TILE_CHUNKS / NT;        // chunks per thread per tile, K and V each
-  static_assert(TILE_CHUNKS % NT == 0, "tile must divide over the workgroup");
+  constexpr int TILE_BYTES = BN * D * 2;
+  constexpr int UNITS = TILE_BYTES / 1024;       // wave-wide 1 KB copies per tile (K or V)
+  constexpr int KPU = 1024 / (D * 2);            // keys per copy
+  static_assert(UNITS % NW == 0, "copies must divide over the waves");
+  constexpr int UPW = UNITS / NW;                // copies per wave per tile (K and V each)
   constexpr int KK = D / 16;                     // MFMA k-steps over the head dim
   constexpr int DB = D / 32;                     // 32-wide head-dim blocks of O^T
 
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds[BN * D * 2];
-  __shared__ __attribute__((aligned(16))) unsigned char v_lds[BN * D * 2];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2][2][TILE_BYTES];   // [buffer][K,V]
 
   const AttnItem it = items[blockIdx.x];
   const int G = Hq / Hkv;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31;
   const int hh = lane >> 5;
   const int P = it.prefix, S = it.suffix;
@@ -169,42 +183,65 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_kernel(
     l_run[rb] = 0.f;
   }
 
-  // ---- staging: thread moves chunks tid + j*NT of the tile
-  u32x4 kreg[LOADS], vreg[LOADS];
-  auto fetch = [&](int key0) {
+  // ---- paged copy: wave w moves units w, w+NW, ...; a unit is KPU whole key
+  // rows of one page.  Lane l fills LDS slot (row l/CPR, chunk l%CPR) of the
+  // unit and therefore fetches chunk (l%CPR) ^ swz(row).
+  const int64_t head_off = (int64_t)it.kv_head * (kPage * D * 2);
+  const int64_t page_stride = (int64_t)Hkv * (kPage * D * 2);
+  int lane_src[UPW];                              // byte offset inside the (page, head) block
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const int c = tid + j * NT;
-      const int key = c / CPR;                    // 0..63 inside the tile
-      int blk = (key0 + key) / kPage;
-      if (blk > nblk - 1) blk = nblk - 1;         // never read a table entry past the sequence
-      const int32_t page = bt[blk];
-      const int64_t src = (((int64_t)page * Hkv + it.kv_head) * kPage + (key % kPage)) * CPR + (c % CPR);
-      kreg[j] = reinterpret_cast<const u32x4 *>(k_pool)[src];
-      vreg[j] = reinterpret_cast<const u32x4 *>(v_pool)[src];
-    }
+  for (int i = 0; i < UPW; ++i) {
+    const int u = wave + NW * i;
+    const int key = u * KPU + lane / CPR;         // key inside the tile
+    lane_src[i] = (key % kPage) * (D * 2) + (((lane % CPR) ^ swz<D>(key)) << 4);
+  }
+  auto page_of = [&](int key0, int i) -> int32_t {
+    int blk = (key0 + (wave + NW * i) * KPU) / kPage;
+    if (blk > nblk - 1) blk = nblk - 1;           // never read a table entry past the sequence
+    return bt[blk];
   };
-  auto stash = [&](int key0) {
+  auto copy_tile = [&](int buf, const int32_t (&pages)[UPW]) {
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const int c = tid + j * NT;
-      const int key = c / CPR;
-      const int off = lds_off<D>(key, c % CPR);
-      u32x4 vv = vreg[j];
-      if (key0 + key >= T) vv = u32x4{0u, 0u, 0u, 0u};   // slots past the sequence hold no data
-      *reinterpret_cast<u32x4 *>(k_lds + off) = kreg[j];
-      *reinterpret_cast<u32x4 *>(v_lds + off) = vv;
+    for (int i = 0; i < UPW; ++i) {
+      const int u = wave + NW * i;
+      const int64_t src = (int64_t)pages[i] * page_stride + head_off + lane_src[i];
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)((const unsigned char *)k_pool + src),
+          (__attribute__((address_space(3))) void *)(&lds[buf][0][u * 1024]), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)((const unsigned char *)v_pool + src),
+          (__attribute__((address_space(3))) void *)(&lds[buf][1][u * 1024]), 16, 0, 0);
     }
   };
 
   const int kv_begin = it.kv_begin, kv_end = it.kv_end;
-  if (kv_begin < kv_end) fetch(kv_begin);
+  int32_t pages[UPW];
+  if (kv_begin < kv_end) {
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) pages[i] = page_of(kv_begin, i);
+    copy_tile(0, pages);
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) pages[i] = page_of(kv_begin + BN, i);
+  }
 
-  for (int key0 = kv_begin; key0 < kv_end; key0 += BN) {
-    __syncthreads();                              // all waves are done with the previous tile
-    stash(key0);
-    __syncthreads();
-    if (key0 + BN < kv_end) fetch(key0 + BN);
+  int buf = 0;
+  for (int key0 = kv_begin; key0 < kv_end; key0 += BN, buf ^= 1) {
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the tile has landed
+    __syncthreads();                              // everyone's has; the other buffer is free again
+    if (key0 + BN < kv_end) {
+      copy_tile(buf ^ 1, pages);
+#pragma unroll
+      for (int i = 0; i < UPW; ++i) pages[i] = page_of(key0 + 2 * BN, i);
+    }
+    unsigned char *k_lds = &lds[buf][0][0];
+    unsigned char *v_lds = &lds[buf][1][0];
+    if (key0 + BN > T) {
+      // Slots past the end of the sequence hold whatever the pool held: clear
+      // those V rows so that 0 * garbage cannot poison the products.
+      for (int c = tid; c < BN * CPR; c += NT)
+        if (key0 + c / CPR >= T) *reinterpret_cast<u32x4 *>(v_lds + c * 16) = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+    }
 
     if (!wave_live || key0 > hi_limit) continue;  // nothing visible to this wave in the tile
 
@@ -250,10 +287,18 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][rb][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[rb], mx);
-      const float alpha = fast_exp2((m_run[rb] - m_new) * scale_log2e);
-      const float mc = m_new * scale_log2e;
-      m_run[rb] = m_new;
+      const bool grow = (mx - m_run[rb]) * scale_log2e > kRescaleThreshold;
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        const float m_new = fmaxf(m_run[rb], mx);
+        const float alpha = fast_exp2((m_run[rb] - m_new) * scale_log2e);
+        m_run[rb] = m_new;
+        l_run[rb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][rb][r] *= alpha;
+      }
+      const float mc = m_run[rb] * scale_log2e;
       float sum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < BN / 32; ++kb)
@@ -263,11 +308,7 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_kernel(
           sacc[kb][rb][r] = pv;
           sum += pv;
         }
-      l_run[rb] = l_run[rb] * alpha + sum;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][rb][r] *= alpha;
+      l_run[rb] += sum;
     }
 
     // ---- O^T += V^T P^T
@@ -396,9 +437,9 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(
   *reinterpret_cast<bf16x4 *>(op) = o4;
 }
 
-template <int D, int RB, int NW>
+template <int D, int RB, int NW, int WPE>
 static int launch_attn_t(const LaunchParams &p, hipStream_t st) {
-  hipLaunchKernelGGL((prefill_attn_kernel<D, RB, NW>), dim3((unsigned)p.num_items), dim3(NW * 64), 0,
+  hipLaunchKernelGGL((prefill_attn_kernel<D, RB, NW, WPE>), dim3((unsigned)p.num_items), dim3(NW * 64), 0,
                      st, (const __bf16 *)p.q, (const __bf16 *)p.k_pool, (const __bf16 *)p.v_pool,
                      p.block_table, (__bf16 *)p.out, p.partials, p.items, p.Hq, p.Hkv, p.max_blocks,
                      p.scale_log2e);
@@ -409,13 +450,13 @@ int launch_attention(const LaunchParams &p, void *stream) {
   if (p.num_items == 0) return 0;
   hipStream_t st = (hipStream_t)stream;
   if (p.d == 128) {
-    if (p.tile_rows == 64) return launch_attn_t<128, 1, 2>(p, st);
-    if (p.tile_rows == 128) return launch_attn_t<128, 1, 4>(p, st);
-    return launch_attn_t<128, 2, 4>(p, st);
+    if (p.tile_rows == 64) return launch_attn_t<128, 1, 2, 2>(p, st);
+    if (p.tile_rows == 128) return launch_attn_t<128, 1, 4, 2>(p, st);
+    return launch_attn_t<128, 2, 4, 1>(p, st);
   }
-  if (p.tile_rows == 64) return launch_attn_t<64, 1, 2>(p, st);
-  if (p.tile_rows == 128) return launch_attn_t<64, 1, 4>(p, st);
-  return launch_attn_t<64, 2, 4>(p, st);
+  if (p.tile_rows == 64) return launch_attn_t<64, 1, 2, 2>(p, st);
+  if (p.tile_rows == 128) return launch_attn_t<64, 1, 4, 2>(p, st);
+  return launch_attn_t<64, 2, 4, 1>(p, st);
 }
 
 int launch_reduce(const LaunchParams &p, void *stream) {
