@@ -115,8 +115,9 @@ int prism_plan_create(const prism_shape_t *shape, const int32_t *prefix_len_host
  * The same schedule computed on the host only (no device is touched): fills
  * info and, when items_out is not NULL, up to items_capacity work items as
  * 8 int32 each: request, kv head, first packed row, kv_begin, kv_end,
- * partial slot (-1 = writes out directly), prefix, suffix.  Returns the
- * number of items (>= 0) or an error code.  For tests and capacity planning.
+ * partial slot (-1 = writes out directly), prefix, suffix.  Entries with
+ * request -1 are idle padding that keeps the die interleave aligned.  Returns
+ * the number of items (>= 0) or an error code.  For tests and capacity planning.
  */
 int prism_plan_dry_run(const prism_shape_t *shape, const int32_t *prefix_len_host,
                        const int32_t *suffix_len_host, const prism_plan_options_t *options,

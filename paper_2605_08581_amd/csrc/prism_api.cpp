@@ -238,7 +238,7 @@ int prism_plan_dry_run(const prism_shape_t *shape, const int32_t *prefix_len_hos
   if (workspace_bytes) *workspace_bytes = sch.workspace_bytes;
   if (items_out) {
     for (size_t i = 0; i < sch.items.size() && (int32_t)i < items_capacity; ++i) {
-      const AttnItem &it = sch.items[i];
+      const AttnItem &it = sch.items[i];   // idle padding entries have req = -1
       int32_t *o = items_out + 8 * i;
       o[0] = it.req; o[1] = it.kv_head; o[2] = it.row0; o[3] = it.kv_begin;
       o[4] = it.kv_end; o[5] = it.part_slot; o[6] = it.prefix; o[7] = it.suffix;

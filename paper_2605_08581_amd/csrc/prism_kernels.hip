@@ -123,12 +123,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   constexpr int KPU = 1024 / (D * 2);            // keys per copy
   static_assert(UNITS % NW == 0, "copies must divide over the waves");
   constexpr int UPW = UNITS / NW;                // copies per wave per tile (K and V each)
+  constexpr int UPP = (kPage * D * 2) / 1024;    // copies per (page, head) block
+  constexpr int PPW = UPW > UPP ? UPW / UPP : 1; // pages a wave touches per tile
   constexpr int KK = D / 16;                     // MFMA k-steps over the head dim
   constexpr int DB = D / 32;                     // 32-wide head-dim blocks of O^T
 
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2][2][TILE_BYTES];   // [buffer][K,V]
 
   const AttnItem it = items[blockIdx.x];
+  if (it.req < 0) return;                        // idle padding entry
   const int G = Hq / Hkv;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -183,45 +186,49 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     l_run[rb] = 0.f;
   }
 
-  // ---- paged copy: wave w moves units w, w+NW, ...; a unit is KPU whole key
-  // rows of one page.  Lane l fills LDS slot (row l/CPR, chunk l%CPR) of the
-  // unit and therefore fetches chunk (l%CPR) ^ swz(row).
+  // ---- paged copy: wave w moves units w*UPW .. w*UPW+UPW-1 of the tile; a
+  // unit is 1 KB = KPU whole key rows, and consecutive units stay inside one
+  // (page, head) block as long as possible so a wave needs few page ids.
+  // Lane l fills LDS slot (row l/CPR, chunk l%CPR) of the unit and therefore
+  // fetches chunk (l%CPR) ^ swz(row).
   const int64_t head_off = (int64_t)it.kv_head * (kPage * D * 2);
   const int64_t page_stride = (int64_t)Hkv * (kPage * D * 2);
-  int lane_src[UPW];                              // byte offset inside the (page, head) block
+  uint32_t lane_src[UPW];                         // byte offset inside the (page, head) block
 #pragma unroll
   for (int i = 0; i < UPW; ++i) {
-    const int u = wave + NW * i;
-    const int key = u * KPU + lane / CPR;         // key inside the tile
-    lane_src[i] = (key % kPage) * (D * 2) + (((lane % CPR) ^ swz<D>(key)) << 4);
+    const int key = (wave * UPW + i) * KPU + lane / CPR;   // key inside the tile
+    lane_src[i] = (uint32_t)((key % kPage) * (D * 2) + (((lane % CPR) ^ swz<D>(key)) << 4));
   }
-  auto page_of = [&](int key0, int i) -> int32_t {
-    int blk = (key0 + (wave + NW * i) * KPU) / kPage;
+  const int wave_blk = (wave * UPW) / UPP;        // first page of the tile this wave copies from
+  auto page_of = [&](int key0, int j) -> int32_t {
+    int blk = key0 / kPage + wave_blk + j;
     if (blk > nblk - 1) blk = nblk - 1;           // never read a table entry past the sequence
     return bt[blk];
   };
-  auto copy_tile = [&](int buf, const int32_t (&pages)[UPW]) {
+  auto copy_tile = [&](int buf, const int32_t (&pages)[PPW]) {
 #pragma unroll
     for (int i = 0; i < UPW; ++i) {
-      const int u = wave + NW * i;
-      const int64_t src = (int64_t)pages[i] * page_stride + head_off + lane_src[i];
+      const int u = wave * UPW + i;
+      const int64_t base = (int64_t)pages[i / UPP] * page_stride + head_off;   // wave-uniform
+      const unsigned char *ksrc = (const unsigned char *)k_pool + base;
+      const unsigned char *vsrc = (const unsigned char *)v_pool + base;
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)((const unsigned char *)k_pool + src),
+          (const __attribute__((address_space(1))) void *)(ksrc + lane_src[i]),
           (__attribute__((address_space(3))) void *)(&lds[buf][0][u * 1024]), 16, 0, 0);
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)((const unsigned char *)v_pool + src),
+          (const __attribute__((address_space(1))) void *)(vsrc + lane_src[i]),
           (__attribute__((address_space(3))) void *)(&lds[buf][1][u * 1024]), 16, 0, 0);
     }
   };
 
   const int kv_begin = it.kv_begin, kv_end = it.kv_end;
-  int32_t pages[UPW];
+  int32_t pages[PPW];
   if (kv_begin < kv_end) {
 #pragma unroll
-    for (int i = 0; i < UPW; ++i) pages[i] = page_of(kv_begin, i);
+    for (int j = 0; j < PPW; ++j) pages[j] = page_of(kv_begin, j);
     copy_tile(0, pages);
 #pragma unroll
-    for (int i = 0; i < UPW; ++i) pages[i] = page_of(kv_begin + BN, i);
+    for (int j = 0; j < PPW; ++j) pages[j] = page_of(kv_begin + BN, j);
   }
 
   int buf = 0;
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     if (key0 + BN < kv_end) {
       copy_tile(buf ^ 1, pages);
 #pragma unroll
-      for (int i = 0; i < UPW; ++i) pages[i] = page_of(key0 + 2 * BN, i);
+      for (int j = 0; j < PPW; ++j) pages[j] = page_of(key0 + 2 * BN, j);
     }
     unsigned char *k_lds = &lds[buf][0][0];
     unsigned char *v_lds = &lds[buf][1][0];

@@ -105,47 +105,77 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
     return a.row0 > b.row0;
   });
 
+  // Workgroup b runs on accelerator die b % 8, and each die has its own L2.
+  // Row tiles (and key chunks) of one (request, kv head) read the same K/V
+  // pages, so each such group is dealt whole to one die - the least loaded so
+  // far, heaviest groups first - and the per-die lists are then interleaved
+  // so that list position k of die x becomes workgroup 8k + x.
+  std::vector<AttnItem> per_die[kNumXCD];
+  int64_t die_load[kNumXCD] = {0};
   int next_slot = 0;
-  for (const RowTile &t : tiles) {
-    int nsplit = 1;
-    if (opt.split_kv > 1) {
-      nsplit = std::min(opt.split_kv, t.cost);
-    } else if (opt.split_kv == 0 && t.cost >= 2 * chunk) {
-      nsplit = (t.cost + chunk - 1) / chunk;
-    }
-    AttnItem it{};
-    it.req = t.req;
-    it.kv_head = t.kv_head;
-    it.row0 = t.row0;
-    it.prefix = prefix[t.req];
-    it.suffix = suffix[t.req];
-    it.q_off = q_off[t.req];
-    if (nsplit <= 1) {
-      it.kv_begin = 0;
-      it.kv_end = t.kv_len;
-      it.part_slot = -1;
-      sch.items.push_back(it);
-      continue;
-    }
-    const int per = (t.cost + nsplit - 1) / nsplit;   // key tiles per chunk
-    nsplit = (t.cost + per - 1) / per;
-    ReduceGroup g{};
-    g.req = t.req;
-    g.kv_head = t.kv_head;
-    g.row0 = t.row0;
-    g.nsplit = nsplit;
-    g.first_slot = next_slot;
-    g.suffix = suffix[t.req];
-    g.q_off = q_off[t.req];
-    sch.groups.push_back(g);
-    for (int c = 0; c < nsplit; ++c) {
-      it.kv_begin = c * per * kTileKeys;
-      it.kv_end = std::min(t.kv_len, (c + 1) * per * kTileKeys);
-      it.part_slot = next_slot++;
-      sch.items.push_back(it);
-      ++sch.num_split_items;
+  size_t i = 0;
+  while (i < tiles.size()) {
+    size_t j = i;
+    int64_t group_cost = 0;
+    while (j < tiles.size() && tiles[j].req == tiles[i].req && tiles[j].kv_head == tiles[i].kv_head)
+      group_cost += tiles[j++].cost;
+    int die = 0;
+    for (int x = 1; x < kNumXCD; ++x)
+      if (die_load[x] < die_load[die]) die = x;
+    die_load[die] += group_cost;
+    for (; i < j; ++i) {
+      const RowTile &t = tiles[i];
+      int nsplit = 1;
+      if (opt.split_kv > 1) {
+        nsplit = std::min(opt.split_kv, t.cost);
+      } else if (opt.split_kv == 0 && t.cost >= 2 * chunk) {
+        nsplit = (t.cost + chunk - 1) / chunk;
+      }
+      AttnItem it{};
+      it.req = t.req;
+      it.kv_head = t.kv_head;
+      it.row0 = t.row0;
+      it.prefix = prefix[t.req];
+      it.suffix = suffix[t.req];
+      it.q_off = q_off[t.req];
+      if (nsplit <= 1) {
+        it.kv_begin = 0;
+        it.kv_end = t.kv_len;
+        it.part_slot = -1;
+        per_die[die].push_back(it);
+        continue;
+      }
+      const int per = (t.cost + nsplit - 1) / nsplit;   // key tiles per chunk
+      nsplit = (t.cost + per - 1) / per;
+      ReduceGroup g{};
+      g.req = t.req;
+      g.kv_head = t.kv_head;
+      g.row0 = t.row0;
+      g.nsplit = nsplit;
+      g.first_slot = next_slot;
+      g.suffix = suffix[t.req];
+      g.q_off = q_off[t.req];
+      sch.groups.push_back(g);
+      for (int c = 0; c < nsplit; ++c) {
+        it.kv_begin = c * per * kTileKeys;
+        it.kv_end = std::min(t.kv_len, (c + 1) * per * kTileKeys);
+        it.part_slot = next_slot++;
+        per_die[die].push_back(it);
+        ++sch.num_split_items;
+      }
     }
   }
+  size_t longest = 0;
+  for (int x = 0; x < kNumXCD; ++x) longest = std::max(longest, per_die[x].size());
+  AttnItem idle{};
+  idle.req = -1;                 // the kernel returns at once on such an entry
+  idle.part_slot = -1;
+  for (size_t k = 0; k < longest; ++k)
+    for (int x = 0; x < kNumXCD; ++x) {
+      sch.items.push_back(k < per_die[x].size() ? per_die[x][k] : idle);
+    }
+  // drop idle entries at the very end of the list
+  while (!sch.items.empty() && sch.items.back().req < 0) sch.items.pop_back();
   sch.num_slots = next_slot;
   sch.workspace_bytes = (size_t)next_slot * partial_slot_bytes(tile_rows, d);
   *out = std::move(sch);

@@ -70,7 +70,11 @@ def _check_cover(b, tile_rows, split_kv, min_split_keys=0):
     assert info.tile_keys == 64 and info.num_items == len(items)
     cover = {}
     slots = set()
-    for req, kvh, row0, kb, ke, slot, P, S in items.tolist():
+    die = {}
+    for pos, (req, kvh, row0, kb, ke, slot, P, S) in enumerate(items.tolist()):
+        if req < 0:
+            continue                     # idle padding of the die interleave
+        die.setdefault((req, kvh), set()).add(pos % 8)
         assert P == b.prefix_len[req] and S == b.suffix_len[req]
         assert row0 % tr == 0 and 0 <= row0 < S * G
         last_row = min(S * G, row0 + tr) - 1
@@ -80,6 +84,7 @@ def _check_cover(b, tile_rows, split_kv, min_split_keys=0):
         if slot >= 0:
             assert slot not in slots
             slots.add(slot)
+    assert all(len(v) == 1 for v in die.values()), "one (request, kv head) must stay on one die"
     want = {(r, h, t * tr) for r in range(b.batch) for h in range(b.geom.num_kv_heads)
             for t in range(-(-int(b.suffix_len[r]) * G // tr))}
     assert set(cover) == want
