@@ -13,7 +13,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libprism.so")
+LIB_PATH = os.environ.get("PRISM_LIB") or os.path.join(_HERE, "libprism.so")
 _lib = None
 
 PRISM_OK = 0

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "prism_internal.h"
 
 namespace prism {
@@ -66,10 +68,9 @@ int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_po
 //
 // A workgroup of NW waves owns NW*32*RB packed query rows of one (request, kv
 // head) and walks the key range in tiles of 64 keys (four 16-token pages).
-// Each tile's K and V rows are copied from the paged pool straight into LDS
-// (global_load_lds, 16 bytes per lane, no staging registers) into one of two
-// buffers, so the copy of tile t+1 overlaps the math of tile t and there is
-// one workgroup barrier per tile.
+// K and V rows are copied from the paged pool straight into LDS
+// (global_load_lds, 16 bytes per lane, no staging registers); K and V each
+// have a two-slot ring, and there is one workgroup barrier per tile.
 //
 // Per wave the products are taken transposed so that no value ever has to move
 // between lanes except one exchange for the row maximum:
@@ -80,6 +81,11 @@ int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_po
 // rows 8*(r/4) + 4*(l/32) + r%4, r = 0..15 (keys for S^T, head dims for O^T),
 // so the running max, the running sum and the rescale factor of a query row
 // are per-lane scalars.
+//
+// The loop is software pipelined inside each wave: iteration t issues the
+// S^T MFMAs of tile t+1 and the O^T MFMAs of tile t while the vector ALU does
+// the softmax of tile t, so the matrix pipe and the vector pipe of a SIMD work
+// at the same time instead of taking turns.
 //
 // LDS rows are d bf16 wide, 16-byte chunks XOR-swizzled by the key index so
 // that both the row reads (K) and the transposing reads (V) spread over banks.
@@ -106,7 +112,43 @@ __device__ __forceinline__ int lds_off(int key, int chunk) {   // byte offset of
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max over the two 32-lane halves of a wave, result in every lane
+__device__ __forceinline__ float max_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands
+// at lds_base + 16*l (lds_base is wave-uniform and travels in M0).  Inline
+// assembly, so that the compiler does not make later LDS reads of *other*
+// slots wait for these copies; the kernel waits for them itself (s_waitcnt
+// vmcnt(0), then a workgroup barrier) before a slot is read.
+__device__ __forceinline__ void copy16_to_lds(const void *src, uint32_t lds_base) {
+  __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                   :
+                   : "v"(src), "s"(lds_base)
+                   : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
+
+// sched_group_barrier masks
+#define SG_VALU 0x002
+#ifndef EXP_NO_SGB
+#define SGB(a, b) __builtin_amdgcn_sched_group_barrier(a, b, 0)
+#else
+#define SGB(a, b)
+#endif
+#define SG_MFMA 0x008
+#define SG_DSRD 0x100
 
 template <int D, int RB, int NW, int WPE>
 __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
@@ -127,8 +169,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   constexpr int PPW = UPW > UPP ? UPW / UPP : 1; // pages a wave touches per tile
   constexpr int KK = D / 16;                     // MFMA k-steps over the head dim
   constexpr int DB = D / 32;                     // 32-wide head-dim blocks of O^T
+  constexpr int KB = BN / 32;                    // 32-key blocks per tile
+  constexpr int KS = BN / 16;                    // 16-key MFMA k-steps of O^T per tile
 
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[2][2][TILE_BYTES];   // [buffer][K,V]
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2][2][TILE_BYTES];   // [K,V][slot]
 
   const AttnItem it = items[blockIdx.x];
   if (it.req < 0) return;                        // idle padding entry
@@ -163,14 +207,21 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       qf[rb][kk] = v;
     }
   }
-  // Wave-uniform key bounds: below lo_limit no row of the wave is masked,
-  // above hi_limit every row is.
+  // Wave-uniform key bounds: at or below lo_limit no row of the wave is
+  // masked, above hi_limit every row is.
   const int first_row = wrow0 < rows_total ? wrow0 : rows_total - 1;
   int last_row = wrow0 + 32 * RB - 1;
   if (last_row > rows_total - 1) last_row = rows_total - 1;
-  const bool wave_live = wrow0 < rows_total;
   const int lo_limit = P + first_row / G;
   const int hi_limit = P + last_row / G;
+
+  const int kv_begin = it.kv_begin, kv_end = it.kv_end;
+  const int nt = (kv_end - kv_begin + BN - 1) / BN;          // tiles of the workgroup
+  int my_nt = 0;                                             // tiles this wave computes on
+  if (wrow0 < rows_total && hi_limit >= kv_begin) {
+    my_nt = (hi_limit - kv_begin) / BN + 1;
+    if (my_nt > nt) my_nt = nt;
+  }
 
   f32x16 oacc[DB][RB];
 #pragma unroll
@@ -186,8 +237,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     l_run[rb] = 0.f;
   }
 
-  // ---- paged copy: wave w moves units w*UPW .. w*UPW+UPW-1 of the tile; a
-  // unit is 1 KB = KPU whole key rows, and consecutive units stay inside one
+  // ---- paged copy: wave w moves units w*UPW .. w*UPW+UPW-1 of a tile; a unit
+  // is 1 KB = KPU whole key rows, and consecutive units stay inside one
   // (page, head) block as long as possible so a wave needs few page ids.
   // Lane l fills LDS slot (row l/CPR, chunk l%CPR) of the unit and therefore
   // fetches chunk (l%CPR) ^ swz(row).
@@ -199,104 +250,87 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     const int key = (wave * UPW + i) * KPU + lane / CPR;   // key inside the tile
     lane_src[i] = (uint32_t)((key % kPage) * (D * 2) + (((lane % CPR) ^ swz<D>(key)) << 4));
   }
-  const int wave_blk = (wave * UPW) / UPP;        // first page of the tile this wave copies from
-  auto page_of = [&](int key0, int j) -> int32_t {
-    int blk = key0 / kPage + wave_blk + j;
-    if (blk > nblk - 1) blk = nblk - 1;           // never read a table entry past the sequence
-    return bt[blk];
+  const uint32_t lds_base = lds_address(&lds[0][0][0]);
+  const int wave_blk = (wave * UPW) / UPP;        // first page of a tile this wave copies from
+  struct PageIds {
+    int32_t p[PPW];
   };
-  auto copy_tile = [&](int buf, const int32_t (&pages)[PPW]) {
+  auto pages_of = [&](int t) -> PageIds {         // page ids of tile t for this wave
+    PageIds r;
+#pragma unroll
+    for (int j = 0; j < PPW; ++j) {
+      int blk = (kv_begin + t * BN) / kPage + wave_blk + j;
+      if (blk > nblk - 1) blk = nblk - 1;         // never read a table entry past the sequence
+      r.p[j] = bt[blk];
+    }
+    return r;
+  };
+  auto copy_rows = [&](const void *pool, int which, int slot, const PageIds &pg) {
 #pragma unroll
     for (int i = 0; i < UPW; ++i) {
       const int u = wave * UPW + i;
-      const int64_t base = (int64_t)pages[i / UPP] * page_stride + head_off;   // wave-uniform
-      const unsigned char *ksrc = (const unsigned char *)k_pool + base;
-      const unsigned char *vsrc = (const unsigned char *)v_pool + base;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)(ksrc + lane_src[i]),
-          (__attribute__((address_space(3))) void *)(&lds[buf][0][u * 1024]), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)(vsrc + lane_src[i]),
-          (__attribute__((address_space(3))) void *)(&lds[buf][1][u * 1024]), 16, 0, 0);
+      const int64_t base = (int64_t)pg.p[i / UPP] * page_stride + head_off;   // wave-uniform
+      copy16_to_lds((const unsigned char *)pool + base + lane_src[i],
+                    lds_base + (uint32_t)((which * 2 + slot) * TILE_BYTES + u * 1024));
     }
   };
 
-  const int kv_begin = it.kv_begin, kv_end = it.kv_end;
-  int32_t pages[PPW];
-  if (kv_begin < kv_end) {
-#pragma unroll
-    for (int j = 0; j < PPW; ++j) pages[j] = page_of(kv_begin, j);
-    copy_tile(0, pages);
-#pragma unroll
-    for (int j = 0; j < PPW; ++j) pages[j] = page_of(kv_begin + BN, j);
-  }
+  const int i16 = lane & 15;
+  const int grp = (lane >> 4) & 1;
+  f32x16 s_buf[2][KB][RB];                        // S^T of the current and of the next tile
 
-  int buf = 0;
-  for (int key0 = kv_begin; key0 < kv_end; key0 += BN, buf ^= 1) {
-    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the tile has landed
-    __syncthreads();                              // everyone's has; the other buffer is free again
-    if (key0 + BN < kv_end) {
-      copy_tile(buf ^ 1, pages);
+  // K fragment i (0 .. KB*KK-1) of a tile: rows kb*32+l32, dims 16kk+8hh..+7
+  auto k_frag = [&](const unsigned char *k_lds, int i) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8 *>(k_lds + lds_off<D>((i / KK) * 32 + l32, 2 * (i % KK) + hh));
+  };
+  // V^T fragment j (0 .. KS*DB-1): head dims 32db+l32, keys of k-step ks.
+  // Transposing read: within 16 lanes, lane i supplies the address of 4 head
+  // dims 4*(i%4).. of key (i/4); it receives 4 keys of head dim i.
+  auto v_frag = [&](const unsigned char *v_lds, int j) -> bf16x8 {
+    const int ks = j / DB, db = j % DB;
+    const int keyA = 16 * ks + 4 * hh + (i16 >> 2);
+    const int chunk = 4 * db + 2 * grp + ((i16 & 3) >> 1);
+    const int sub = (i16 & 1) << 3;
+    union {
+      s16x4 h[2];
+      bf16x8 v;
+    } a;
+    a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(v_lds + lds_off<D>(keyA, chunk) + sub));
+    a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(v_lds + lds_off<D>(keyA + 8, chunk) + sub));
+    return a.v;
+  };
+  auto mask_tile = [&](f32x16 (&sx)[KB][RB], int key0) {
 #pragma unroll
-      for (int j = 0; j < PPW; ++j) pages[j] = page_of(key0 + 2 * BN, j);
-    }
-    unsigned char *k_lds = &lds[buf][0][0];
-    unsigned char *v_lds = &lds[buf][1][0];
-    if (key0 + BN > T) {
-      // Slots past the end of the sequence hold whatever the pool held: clear
-      // those V rows so that 0 * garbage cannot poison the products.
-      for (int c = tid; c < BN * CPR; c += NT)
-        if (key0 + c / CPR >= T) *reinterpret_cast<u32x4 *>(v_lds + c * 16) = u32x4{0u, 0u, 0u, 0u};
-      __syncthreads();
-    }
-
-    if (!wave_live || key0 > hi_limit) continue;  // nothing visible to this wave in the tile
-
-    // ---- S^T = K Q^T
-    f32x16 sacc[BN / 32][RB];
-#pragma unroll
-    for (int kb = 0; kb < BN / 32; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb][rb][r] = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < BN / 32; ++kb) {
-      const int key = kb * 32 + l32;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(k_lds + lds_off<D>(key, 2 * kk + hh));
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          sacc[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][kk], sacc[kb][rb], 0, 0, 0);
-      }
-    }
-
-    // ---- causal mask (only tiles that reach past the wave's first row)
-    if (key0 + BN - 1 > lo_limit) {
-#pragma unroll
-      for (int kb = 0; kb < BN / 32; ++kb)
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = key0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (key > limit[rb]) sacc[kb][rb][r] = -INFINITY;
-          }
-    }
-
-    // ---- online softmax
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          if (key > limit[rb]) sx[kb][rb][r] = -INFINITY;
+        }
+  };
+  // Row maxima of a score tile; raise the running maximum (and rescale what
+  // has been accumulated) only when some row of the wave needs it.
+  auto raise_max = [&](const f32x16 (&sx)[KB][RB]) {
+    float mx[RB];
+    bool grow = false;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float mx = sacc[0][rb][0];
+      mx[rb] = sx[0][rb][0];
 #pragma unroll
-      for (int kb = 0; kb < BN / 32; ++kb)
+      for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][rb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const bool grow = (mx - m_run[rb]) * scale_log2e > kRescaleThreshold;
-      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-        const float m_new = fmaxf(m_run[rb], mx);
+        for (int r = 0; r < 16; ++r) mx[rb] = fmaxf(mx[rb], sx[kb][rb][r]);
+      mx[rb] = max_across_halves(mx[rb]);
+      grow |= (mx[rb] - m_run[rb]) * scale_log2e > kRescaleThreshold;
+    }
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        const float m_new = fmaxf(m_run[rb], mx[rb]);
         const float alpha = fast_exp2((m_run[rb] - m_new) * scale_log2e);
         m_run[rb] = m_new;
         l_run[rb] *= alpha;
@@ -305,51 +339,198 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[db][rb][r] *= alpha;
       }
-      const float mc = m_run[rb] * scale_log2e;
-      float sum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < BN / 32; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float pv = fast_exp2(fmaf(sacc[kb][rb][r], scale_log2e, -mc));
-          sacc[kb][rb][r] = pv;
-          sum += pv;
-        }
-      l_run[rb] += sum;
     }
-
-    // ---- O^T += V^T P^T
+  };
+  // P^T fragment of k-step ks from the scores (exp2, row sums, bf16 rounding)
+  auto p_frag = [&](const f32x16 (&sx)[KB][RB], int ks, int rb, float mc) -> bf16x8 {
+    bf16x8 pf;
+    float sum = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < BN / 16; ++ks) {
-      bf16x8 pf[RB];
+    for (int e = 0; e < 8; ++e) {
+      const float pv = fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e], scale_log2e, -mc));
+      sum += pv;
+      pf[e] = (__bf16)pv;
+    }
+    l_run[rb] += sum;
+    return pf;
+  };
+
+  // Scores of one tile, not overlapped with anything (first tile, and tiles
+  // that need the causal mask).
+  auto plain_scores = [&](f32x16 (&sx)[KB][RB], const unsigned char *k_lds, int key0, bool masked) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[rb][e] = (__bf16)sacc[ks >> 1][rb][8 * (ks & 1) + e];
-      // Transposing read: within 16 lanes, lane i supplies the address of 4
-      // head dims 4*(i%4).. of key (i/4); it receives 4 keys of head dim i.
-      const int i16 = lane & 15;
-      const int grp = (lane >> 4) & 1;
-      const int keyA = 16 * ks + 4 * hh + (i16 >> 2);
-      const int keyB = keyA + 8;
+        for (int r = 0; r < 16; ++r) sx[kb][rb][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < KB * KK; ++i) {
+      const bf16x8 a = k_frag(k_lds, i);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        sx[i / KK][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][i % KK], sx[i / KK][rb], 0, 0, 0);
+    }
+    if (masked) mask_tile(sx, key0);
+    raise_max(sx);
+  };
+  // Softmax and O^T update of the current tile, nothing overlapped (tiles on
+  // the causal diagonal and the last tile).
+  auto tail_step = [&](f32x16 (&sc)[KB][RB], const unsigned char *v_cur) {
+    float mc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) mc[rb] = m_run[rb] * scale_log2e;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 pf[RB];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) pf[rb] = p_frag(sc, ks, rb, mc[rb]);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const int chunk = 4 * db + 2 * grp + ((i16 & 3) >> 1);
-        const int sub = (i16 & 1) << 3;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4 *)(v_lds + lds_off<D>(keyA, chunk) + sub));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4 *)(v_lds + lds_off<D>(keyB, chunk) + sub));
-        union {
-          s16x4 h[2];
-          bf16x8 v;
-        } a;
-        a.h[0] = lo;
-        a.h[1] = hi;
+        const bf16x8 a = v_frag(v_cur, ks * DB + db);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-          oacc[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pf[rb], oacc[db][rb], 0, 0, 0);
+          oacc[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb], oacc[db][rb], 0, 0, 0);
       }
+    }
+  };
+
+  // The overlapped step: scores of the next (unmasked) tile into sn, softmax
+  // of the current tile sc, O^T += V^T P^T.  The work is laid out as a chain
+  // of chunks - one MFMA, one LDS fragment read three chunks ahead of its
+  // use, and a slice of the exponentials - and the compiler's scheduler is
+  // fenced between chunks, so the matrix pipe always has an MFMA queued while
+  // the vector ALU works through the softmax.
+  constexpr int NQK = KB * KK;                    // S^T MFMAs per tile (per row block)
+  constexpr int NPV = KS * DB;                    // O^T MFMAs per tile
+  constexpr int NEL = KB * 16;                    // score elements per lane per row block
+  constexpr int LA = 3;                           // fragment reads run this many chunks ahead
+  constexpr int CSPAN = NQK + (KS - 1) * DB;      // chunks over which the exponentials spread
+  auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], const unsigned char *k_next,
+                  const unsigned char *v_cur) {
+    static_assert(RB == 1, "the overlapped step is written for one 32-row block per wave");
+    const float mc = m_run[0] * scale_log2e;
+    float sum = 0.f;
+    bf16x8 frag[LA + 1];                          // ring of K / V^T fragments in flight
+    bf16x8 pf[2];                                 // P^T fragments: the one in use and the next
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sn[kb][0][r] = 0.f;
+    auto fetch = [&](int i) {                     // fragment i of the chain: K first, then V^T
+      if (i < NQK) frag[i % (LA + 1)] = k_frag(k_next, i);
+      else if (i < NQK + NPV) frag[i % (LA + 1)] = v_frag(v_cur, i - NQK);
+    };
+    auto softmax_slice = [&](int c) {             // the exponentials that belong to chunk c
+      if (c >= CSPAN) return;
+      const int e0 = (c * NEL + CSPAN - 1) / CSPAN, e1 = ((c + 1) * NEL + CSPAN - 1) / CSPAN;
+#pragma unroll
+      for (int e = e0; e < e1; ++e) {
+        const float pv = fast_exp2(fmaf(sc[e / 16][0][e % 16], scale_log2e, -mc));
+        sc[e / 16][0][e % 16] = pv;
+        sum += pv;
+        if (e % 8 == 7) {                         // a whole 16-key k-step is ready: round it
+          const int ks = e / 8;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) pf[ks & 1][x] = (__bf16)sc[ks >> 1][0][8 * (ks & 1) + x];
+        }
+      }
+    };
+#pragma unroll
+    for (int i = 0; i < LA; ++i) fetch(i);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int c = 0; c < NQK + NPV; ++c) {
+      fetch(c + LA);
+      if (c < NQK) {
+        sn[c / KK][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], qf[0][c % KK],
+                                                                sn[c / KK][0], 0, 0, 0);
+      } else {
+        const int j = c - NQK;
+        oacc[j % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], pf[(j / DB) & 1],
+                                                                  oacc[j % DB][0], 0, 0, 0);
+      }
+      softmax_slice(c);
+      if (c < NQK + NPV - DB) __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run[0] += sum;
+    raise_max(sn);
+  };
+
+  // ---- main loop.  At the start of iteration t the scores of tile t are in
+  // registers, K of tile t+1 and V of tile t are in LDS; the iteration starts
+  // the copies of K of tile t+2 and V of tile t+1 into the slots that
+  // iteration t-1 finished with, and ends with the scores of tile t+1.
+  const bool wave_live = my_nt > 0;
+  f32x16 s_a[KB][RB], s_b[KB][RB];
+  PageIds pg_v, pg_k, pg_n;                       // page ids of tiles t+1, t+2, t+3
+  if (nt > 0) {
+    const PageIds pg0 = pages_of(0);
+    copy_rows(k_pool, 0, 0, pg0);
+    copy_rows(v_pool, 1, 0, pg0);
+    pg_v = pages_of(1);
+    if (nt > 1) copy_rows(k_pool, 0, 1, pg_v);
+    pg_k = pages_of(2);
+    pg_n = pages_of(3);
+    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
+    __syncthreads();
+    if (wave_live) plain_scores(s_a, &lds[0][0][0], kv_begin, kv_begin + BN - 1 > lo_limit);
+  }
+  auto tile_header = [&](int t) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this wave's copies have landed
+    __syncthreads();                              // everyone's have; iteration t-1 is over
+    if (t + 2 < nt) copy_rows(k_pool, 0, t & 1, pg_k);
+    if (t + 1 < nt) copy_rows(v_pool, 1, (t + 1) & 1, pg_v);
+    pg_v = pg_k;
+    pg_k = pg_n;
+    pg_n = pages_of(t + 4);
+  };
+
+  // Tiles 0 .. n_fast-1 are followed by a tile that no row of the workgroup
+  // needs masked: they run the overlapped step, two per trip so that the two
+  // score buffers swap roles without copies.
+  int n_fast = 0;
+  {
+    const int blk_limit = P + it.row0 / G;        // last key visible to the workgroup's first row
+    if (blk_limit >= kv_begin + 2 * BN - 1) n_fast = (blk_limit + 1 - kv_begin) / BN - 1;
+    if (n_fast > nt - 1) n_fast = nt - 1;
+    if (n_fast < 0) n_fast = 0;
+  }
+  int t = 0;
+  for (; t + 1 < n_fast; t += 2) {
+    tile_header(t);
+    if (wave_live) step(s_a, s_b, &lds[0][1][0], &lds[1][0][0]);
+    tile_header(t + 1);
+    if (wave_live) step(s_b, s_a, &lds[0][0][0], &lds[1][1][0]);
+  }
+  if (t < n_fast) {                               // n_fast is odd: t is even here
+    tile_header(t);
+    if (wave_live) {
+      step(s_a, s_b, &lds[0][1][0], &lds[1][0][0]);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) s_a[kb][rb] = s_b[kb][rb];
+    }
+    ++t;
+  }
+  // Remaining tiles (the causal diagonal and the end of the sequence), one at
+  // a time without overlap; s_a holds the scores of tile t.
+  for (; t < nt; ++t) {
+    const int key0 = kv_begin + t * BN;
+    tile_header(t);
+    unsigned char *v_cur = &lds[1][t & 1][0];
+    if (key0 + BN > T) {
+      // Slots past the end of the sequence hold whatever the pool held: clear
+      // those V rows so that 0 * garbage cannot poison the products.
+      for (int c = tid; c < BN * CPR; c += NT)
+        if (key0 + c / CPR >= T) *reinterpret_cast<u32x4 *>(v_cur + c * 16) = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+    }
+    if (t < my_nt) {
+      tail_step(s_a, v_cur);
+      if (t + 1 < my_nt)
+        plain_scores(s_a, &lds[0][(t + 1) & 1][0], key0 + BN, key0 + 2 * BN - 1 > lo_limit);
     }
   }
 
@@ -357,7 +538,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int row = wrow0 + rb * 32 + l32;
-    const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
+    const float l_tot = sum_across_halves(l_run[rb]);
     if (row >= rows_total) continue;
     if (it.part_slot < 0) {
       const float inv = 1.0f / l_tot;
@@ -459,11 +640,11 @@ int launch_attention(const LaunchParams &p, void *stream) {
   if (p.d == 128) {
     if (p.tile_rows == 64) return launch_attn_t<128, 1, 2, 2>(p, st);
     if (p.tile_rows == 128) return launch_attn_t<128, 1, 4, 2>(p, st);
-    return launch_attn_t<128, 2, 4, 1>(p, st);
+    return launch_attn_t<128, 1, 8, 2>(p, st);
   }
   if (p.tile_rows == 64) return launch_attn_t<64, 1, 2, 2>(p, st);
   if (p.tile_rows == 128) return launch_attn_t<64, 1, 4, 2>(p, st);
-  return launch_attn_t<64, 2, 4, 1>(p, st);
+  return launch_attn_t<64, 1, 8, 2>(p, st);
 }
 
 int launch_reduce(const LaunchParams &p, void *stream) {
