@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--split-kv", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of this many MiB (read + write), for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -90,6 +93,15 @@ def main():
         sys.exit(2)
     B.load()
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = args.calibrate_copy * 2**20
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n}))
+        return
 
     if args.config == 3 and args.hit is not None:
         b = W.make_hit_rate_batch(args.hit)
@@ -143,7 +155,11 @@ def main():
     try:
         with open(args.traffic_json) as f:
             tj = json.load(f)
-        if tj.get("workload") == b.name and tj.get("kernel_rev") == B.prism_version():
+        import hashlib
+        src = os.path.join(ROOT, "paper_2605_08581_amd", "csrc", "prism_kernels.hip")
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        # counters are only valid for the kernel source they were taken with
+        if tj.get("workload") == b.name and tj.get("kernel_source_sha") == sha:
             traffic = tj.get("bytes_per_launch")
     except (OSError, ValueError):
         pass
