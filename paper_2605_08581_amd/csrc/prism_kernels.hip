@@ -15,6 +15,7 @@ namespace prism {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -123,14 +124,27 @@ __device__ __forceinline__ float sum_across_halves(float x) {
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane l's data lands
-// at lds_base + 16*l (lds_base is wave-uniform and travels in M0).  Inline
-// assembly, so that the compiler does not make later LDS reads of *other*
-// slots wait for these copies; the kernel waits for them itself (s_waitcnt
-// vmcnt(0), then a workgroup barrier) before a slot is read.
-__device__ __forceinline__ void copy16_to_lds(const void *src, uint32_t lds_base) {
-  __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+// at lds_base + 16*l (lds_base is wave-uniform and travels in M0).  The source
+// is a buffer resource (wave-uniform base of one (page, head) block, in scalar
+// registers) plus a per-lane byte offset, which keeps all address arithmetic
+// off the vector ALU and makes a stray offset read zeros instead of faulting.
+// Inline assembly, so that the compiler does not make later LDS reads of
+// *other* slots wait for these copies; the kernel waits for them itself
+// (s_waitcnt vmcnt(0), then a workgroup barrier) before a slot is read.
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+__device__ __forceinline__ i32x4 block_resource(const void *base, uint32_t bytes) {
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  i32x4 r;
+  r[0] = (int32_t)(uint32_t)a;
+  r[1] = (int32_t)(uint32_t)((a >> 32) & 0xFFFFu);   // stride 0: a raw byte buffer
+  r[2] = (int32_t)bytes;                             // offsets at or past this read as zero
+  r[3] = 0x00020000;                                 // 32-bit untyped data
+  return r;
+}
+__device__ __forceinline__ void copy16_to_lds(i32x4 rsrc, uint32_t lane_off, uint32_t lds_base) {
+  __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %0, 0 offen lds"
                    :
-                   : "v"(src), "s"(lds_base)
+                   : "s"(rsrc), "v"(lane_off), "s"(lds_base)
                    : "memory");
 }
 
@@ -269,15 +283,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
 #pragma unroll
     for (int i = 0; i < UPW; ++i) {
       const int u = wave * UPW + i;
-      const int64_t base = (int64_t)pg.p[i / UPP] * page_stride + head_off;   // wave-uniform
-      copy16_to_lds((const unsigned char *)pool + base + lane_src[i],
+      const unsigned char *blk =                                      // wave-uniform
+          (const unsigned char *)pool + (int64_t)pg.p[i / UPP] * page_stride + head_off;
+      copy16_to_lds(block_resource(blk, kPage * D * 2), lane_src[i],
                     lds_base + (uint32_t)((which * 2 + slot) * TILE_BYTES + u * 1024));
     }
   };
 
   const int i16 = lane & 15;
   const int grp = (lane >> 4) & 1;
-  f32x16 s_buf[2][KB][RB];                        // S^T of the current and of the next tile
 
   // K fragment i (0 .. KB*KK-1) of a tile: rows kb*32+l32, dims 16kk+8hh..+7
   auto k_frag = [&](const unsigned char *k_lds, int i) -> bf16x8 {
@@ -344,12 +358,18 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   // P^T fragment of k-step ks from the scores (exp2, row sums, bf16 rounding)
   auto p_frag = [&](const f32x16 (&sx)[KB][RB], int ks, int rb, float mc) -> bf16x8 {
     bf16x8 pf;
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
     float sum = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float pv = fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e], scale_log2e, -mc));
-      sum += pv;
-      pf[e] = (__bf16)pv;
+    for (int e = 0; e < 8; e += 2) {
+      bf16x2 pk;
+      pk[0] = (__bf16)fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e], scale_log2e, -mc));
+      pk[1] = (__bf16)fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e + 1], scale_log2e, -mc));
+      sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);   // sums the rounded values
+      pf[e] = pk[0];
+      pf[e + 1] = pk[1];
     }
     l_run[rb] += sum;
     return pf;
@@ -412,7 +432,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     const float mc = m_run[0] * scale_log2e;
     float sum = 0.f;
     bf16x8 frag[LA + 1];                          // ring of K / V^T fragments in flight
-    bf16x8 pf[2];                                 // P^T fragments: the one in use and the next
+    bf16x8 pf[KS];                                // P^T fragments, one per 16-key k-step
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -421,18 +444,25 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       if (i < NQK) frag[i % (LA + 1)] = k_frag(k_next, i);
       else if (i < NQK + NPV) frag[i % (LA + 1)] = v_frag(v_cur, i - NQK);
     };
-    auto softmax_slice = [&](int c) {             // the exponentials that belong to chunk c
-      if (c >= CSPAN) return;
-      const int e0 = (c * NEL + CSPAN - 1) / CSPAN, e1 = ((c + 1) * NEL + CSPAN - 1) / CSPAN;
+    // Softmax of the current tile, spread over the chunks as a three-stage
+    // pipeline so that no chunk waits on its own results: element e has its
+    // exponent argument formed in chunk home(e)-1, exp2 taken in chunk
+    // home(e), and is rounded to bf16 (two at a time) and added to the row sum
+    // in chunk home(e)+1.  The row sum is taken over the rounded values (dot
+    // product with ones), the same numbers the PV MFMA multiplies.
+    auto home = [](int e) { return 1 + (e * (CSPAN - 2)) / NEL; };
+    auto softmax_slice = [&](int c) {
 #pragma unroll
-      for (int e = e0; e < e1; ++e) {
-        const float pv = fast_exp2(fmaf(sc[e / 16][0][e % 16], scale_log2e, -mc));
-        sc[e / 16][0][e % 16] = pv;
-        sum += pv;
-        if (e % 8 == 7) {                         // a whole 16-key k-step is ready: round it
-          const int ks = e / 8;
-#pragma unroll
-          for (int x = 0; x < 8; ++x) pf[ks & 1][x] = (__bf16)sc[ks >> 1][0][8 * (ks & 1) + x];
+      for (int e = 0; e < NEL; ++e) {
+        if (home(e) == c + 1) sc[e / 16][0][e % 16] = fmaf(sc[e / 16][0][e % 16], scale_log2e, -mc);
+        if (home(e) == c) sc[e / 16][0][e % 16] = fast_exp2(sc[e / 16][0][e % 16]);
+        if ((e & 1) && home(e) == c - 1) {
+          bf16x2 pk;
+          pk[0] = (__bf16)sc[e / 16][0][(e - 1) % 16];
+          pk[1] = (__bf16)sc[e / 16][0][e % 16];
+          sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
+          pf[e / 8][(e % 8) - 1] = pk[0];
+          pf[e / 8][e % 8] = pk[1];
         }
       }
     };
@@ -447,7 +477,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
                                                                 sn[c / KK][0], 0, 0, 0);
       } else {
         const int j = c - NQK;
-        oacc[j % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], pf[(j / DB) & 1],
+        oacc[j % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], pf[j / DB],
                                                                   oacc[j % DB][0], 0, 0, 0);
       }
       softmax_slice(c);
