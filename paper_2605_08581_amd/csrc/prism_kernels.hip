@@ -164,7 +164,7 @@ constexpr float kRescaleThreshold = 8.0f;   // log2 units
 #define SG_MFMA 0x008
 #define SG_DSRD 0x100
 
-template <int D, int RB, int NW, int WPE>
+template <int D, int RB, int NW, int WPE, int NS>
 __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k_pool,
     const __bf16 *__restrict__ v_pool, const int32_t *__restrict__ block_table,
@@ -186,7 +186,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   constexpr int KB = BN / 32;                    // 32-key blocks per tile
   constexpr int KS = BN / 16;                    // 16-key MFMA k-steps of O^T per tile
 
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[2][2][TILE_BYTES];   // [K,V][slot]
+  // LDS: a ring of NS tile slots for K followed by a ring of NS slots for V
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  static_assert(NS >= 2, "each ring needs the slot in use and one being filled");
+  // byte offsets of the ring slots that hold tile t
+  auto k_slot = [&](int t) -> uint32_t { return (uint32_t)(t % NS) * TILE_BYTES; };
+  auto v_slot = [&](int t) -> uint32_t { return (uint32_t)(NS + t % NS) * TILE_BYTES; };
 
   const AttnItem it = items[blockIdx.x];
   if (it.req < 0) return;                        // idle padding entry
@@ -264,7 +269,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     const int key = (wave * UPW + i) * KPU + lane / CPR;   // key inside the tile
     lane_src[i] = (uint32_t)((key % kPage) * (D * 2) + (((lane % CPR) ^ swz<D>(key)) << 4));
   }
-  const uint32_t lds_base = lds_address(&lds[0][0][0]);
+  const uint32_t lds_base = lds_address(lds);
   const int wave_blk = (wave * UPW) / UPP;        // first page of a tile this wave copies from
   struct PageIds {
     int32_t p[PPW];
@@ -286,33 +291,47 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       const unsigned char *blk =                                      // wave-uniform
           (const unsigned char *)pool + (int64_t)pg.p[i / UPP] * page_stride + head_off;
       copy16_to_lds(block_resource(blk, kPage * D * 2), lane_src[i],
-                    lds_base + (uint32_t)((which * 2 + slot) * TILE_BYTES + u * 1024));
+                    lds_base + (uint32_t)((which * NS + slot) * TILE_BYTES + u * 1024));
     }
   };
 
   const int i16 = lane & 15;
   const int grp = (lane >> 4) & 1;
 
-  // K fragment i (0 .. KB*KK-1) of a tile: rows kb*32+l32, dims 16kk+8hh..+7
-  auto k_frag = [&](const unsigned char *k_lds, int i) -> bf16x8 {
-    return *reinterpret_cast<const bf16x8 *>(k_lds + lds_off<D>((i / KK) * 32 + l32, 2 * (i % KK) + hh));
+  // Per-lane LDS addresses of the fragment reads, relative to the start of a
+  // tile slot; everything else (ring slot, 32-key block, k-step) is a constant
+  // added on top, so a read is one address register plus an immediate.
+  typedef __attribute__((address_space(3))) const bf16x8 *lds_b128_ptr;
+  typedef __attribute__((address_space(3))) s16x4 *lds_tr_ptr;
+  uint32_t k_lane[KK];                            // row l32, chunk 2kk+hh
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) k_lane[kk] = lds_base + (uint32_t)lds_off<D>(l32, 2 * kk + hh);
+  uint32_t v_lane[DB][2];                         // key 4hh + i16/4 (+8), 4 head dims of block db
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    const int key = 4 * hh + (i16 >> 2);
+    const int chunk = 4 * db + 2 * grp + ((i16 & 3) >> 1);
+    const int sub = (i16 & 1) << 3;
+    v_lane[db][0] = lds_base + (uint32_t)(lds_off<D>(key, chunk) + sub);
+    v_lane[db][1] = lds_base + (uint32_t)(lds_off<D>(key + 8, chunk) + sub);
+  }
+  // K fragment i (0 .. KB*KK-1) of the tile in K ring slot at byte offset
+  // slot_off: rows kb*32+l32, dims 16kk+8hh..+7
+  auto k_frag = [&](uint32_t slot_off, int i) -> bf16x8 {
+    return *(lds_b128_ptr)(uintptr_t)(k_lane[i % KK] + slot_off + (uint32_t)((i / KK) * 32 * D * 2));
   };
   // V^T fragment j (0 .. KS*DB-1): head dims 32db+l32, keys of k-step ks.
   // Transposing read: within 16 lanes, lane i supplies the address of 4 head
   // dims 4*(i%4).. of key (i/4); it receives 4 keys of head dim i.
-  auto v_frag = [&](const unsigned char *v_lds, int j) -> bf16x8 {
+  auto v_frag = [&](uint32_t slot_off, int j) -> bf16x8 {
     const int ks = j / DB, db = j % DB;
-    const int keyA = 16 * ks + 4 * hh + (i16 >> 2);
-    const int chunk = 4 * db + 2 * grp + ((i16 & 3) >> 1);
-    const int sub = (i16 & 1) << 3;
+    const uint32_t step_off = slot_off + (uint32_t)(ks * 16 * D * 2);
     union {
       s16x4 h[2];
       bf16x8 v;
     } a;
-    a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4 *)(v_lds + lds_off<D>(keyA, chunk) + sub));
-    a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4 *)(v_lds + lds_off<D>(keyA + 8, chunk) + sub));
+    a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(uintptr_t)(v_lane[db][0] + step_off));
+    a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(uintptr_t)(v_lane[db][1] + step_off));
     return a.v;
   };
   auto mask_tile = [&](f32x16 (&sx)[KB][RB], int key0) {
@@ -377,7 +396,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
 
   // Scores of one tile, not overlapped with anything (first tile, and tiles
   // that need the causal mask).
-  auto plain_scores = [&](f32x16 (&sx)[KB][RB], const unsigned char *k_lds, int key0, bool masked) {
+  auto plain_scores = [&](f32x16 (&sx)[KB][RB], uint32_t k_lds, int key0, bool masked) {
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -396,7 +415,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   };
   // Softmax and O^T update of the current tile, nothing overlapped (tiles on
   // the causal diagonal and the last tile).
-  auto tail_step = [&](f32x16 (&sc)[KB][RB], const unsigned char *v_cur) {
+  auto tail_step = [&](f32x16 (&sc)[KB][RB], uint32_t v_cur) {
     float mc[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) mc[rb] = m_run[rb] * scale_log2e;
@@ -426,8 +445,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   constexpr int NEL = KB * 16;                    // score elements per lane per row block
   constexpr int LA = 3;                           // fragment reads run this many chunks ahead
   constexpr int CSPAN = NQK + (KS - 1) * DB;      // chunks over which the exponentials spread
-  auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], const unsigned char *k_next,
-                  const unsigned char *v_cur) {
+  auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], uint32_t k_next,
+                  uint32_t v_cur) __attribute__((always_inline)) {
     static_assert(RB == 1, "the overlapped step is written for one 32-row block per wave");
     const float mc = m_run[0] * scale_log2e;
     float sum = 0.f;
@@ -488,37 +507,66 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   };
 
   // ---- main loop.  At the start of iteration t the scores of tile t are in
-  // registers, K of tile t+1 and V of tile t are in LDS; the iteration starts
-  // the copies of K of tile t+2 and V of tile t+1 into the slots that
-  // iteration t-1 finished with, and ends with the scores of tile t+1.
+  // registers, K of tile t+1 and V of tile t are in LDS, and the copies of the
+  // next NS-2 tiles of each are in flight; the iteration starts the copies of
+  // V of tile t+NS-1 and K of tile t+NS into the slots that iteration t-1
+  // finished with, and ends with the scores of tile t+1.  Copies are issued in
+  // the fixed order K0 V0 K1 V1 ... and complete in that order, so "K of t+1
+  // and V of t have landed" is "at most 2(NS-2) tile copies still pending".
+  // Copies past the end of the key range read the (clamped) last page into a
+  // free slot and are never used: that keeps the pending count uniform.
+  constexpr int PENDING_OK = 2 * (NS - 2) * UPW;
+  static_assert((2 * NS - 2) * UPW <= 63, "pending copies must fit the vmcnt counter");
+  auto wait_pending = [&](auto n_tag) {
+    constexpr int n = decltype(n_tag)::value;
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (n & 15) | ((n >> 4) << 14));   // vmcnt(n) only
+  };
   const bool wave_live = my_nt > 0;
   f32x16 s_a[KB][RB], s_b[KB][RB];
-  PageIds pg_v, pg_k, pg_n;                       // page ids of tiles t+1, t+2, t+3
+  PageIds pg_v, pg_k;                             // page ids of tiles t+NS-1 and t+NS
   if (nt > 0) {
-    const PageIds pg0 = pages_of(0);
-    copy_rows(k_pool, 0, 0, pg0);
-    copy_rows(v_pool, 1, 0, pg0);
-    pg_v = pages_of(1);
-    if (nt > 1) copy_rows(k_pool, 0, 1, pg_v);
-    pg_k = pages_of(2);
-    pg_n = pages_of(3);
-    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
+    PageIds pg = pages_of(0);
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j) {
+      copy_rows(k_pool, 0, j, pg);
+      copy_rows(v_pool, 1, j, pg);
+      pg = pages_of(j + 1);
+    }
+    copy_rows(k_pool, 0, NS - 1, pg);
+    pg_v = pg;
+    pg_k = pages_of(NS);
+    wait_pending(std::integral_constant<int, (2 * NS - 2) * UPW>{});   // K of tile 0 is in
     __syncthreads();
-    if (wave_live) plain_scores(s_a, &lds[0][0][0], kv_begin, kv_begin + BN - 1 > lo_limit);
+    if (wave_live) plain_scores(s_a, k_slot(0), kv_begin, kv_begin + BN - 1 > lo_limit);
   }
-  auto tile_header = [&](int t) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this wave's copies have landed
-    __syncthreads();                              // everyone's have; iteration t-1 is over
-    if (t + 2 < nt) copy_rows(k_pool, 0, t & 1, pg_k);
-    if (t + 1 < nt) copy_rows(v_pool, 1, (t + 1) & 1, pg_v);
+  // j is the tile index modulo NS, known at compile time in the fast loop so
+  // that every LDS address there is a register plus an immediate.
+  auto issue_copies = [&](int v_ring_slot, int k_ring_slot, int t) {
+    copy_rows(v_pool, 1, v_ring_slot, pg_v);
+    copy_rows(k_pool, 0, k_ring_slot, pg_k);
     pg_v = pg_k;
-    pg_k = pg_n;
-    pg_n = pages_of(t + 4);
+    pg_k = pages_of(t + NS + 1);
+  };
+  auto arrive = [&]() {
+    wait_pending(std::integral_constant<int, PENDING_OK>{});   // this wave's part has landed
+    __syncthreads();                              // everyone's has; the previous iteration is over
+  };
+  auto fast_iter = [&](int t, auto j_tag) __attribute__((always_inline)) {
+    constexpr int j = decltype(j_tag)::value;
+    static_assert(NS % 2 == 0, "score buffers alternate with the tile parity");
+    arrive();
+    issue_copies((j + NS - 1) % NS, j, t);
+    if (wave_live) {
+      constexpr uint32_t k_next = (uint32_t)((j + 1) % NS) * TILE_BYTES;
+      constexpr uint32_t v_cur = (uint32_t)(NS + j) * TILE_BYTES;
+      if (j % 2 == 0) step(s_a, s_b, k_next, v_cur);
+      else step(s_b, s_a, k_next, v_cur);
+    }
   };
 
   // Tiles 0 .. n_fast-1 are followed by a tile that no row of the workgroup
-  // needs masked: they run the overlapped step, two per trip so that the two
-  // score buffers swap roles without copies.
+  // needs masked: they run the overlapped step, NS per trip so that ring
+  // slots and score buffers are compile-time choices.
   int n_fast = 0;
   {
     const int blk_limit = P + it.row0 / G;        // last key visible to the workgroup's first row
@@ -527,42 +575,50 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     if (n_fast < 0) n_fast = 0;
   }
   int t = 0;
-  for (; t + 1 < n_fast; t += 2) {
-    tile_header(t);
-    if (wave_live) step(s_a, s_b, &lds[0][1][0], &lds[1][0][0]);
-    tile_header(t + 1);
-    if (wave_live) step(s_b, s_a, &lds[0][0][0], &lds[1][1][0]);
+  for (; t + NS <= n_fast; t += NS) {
+    fast_iter(t, std::integral_constant<int, 0>{});
+    fast_iter(t + 1, std::integral_constant<int, 1>{});
+    if (NS > 2) {
+      fast_iter(t + 2, std::integral_constant<int, 2 % NS>{});
+      fast_iter(t + 3, std::integral_constant<int, 3 % NS>{});
+    }
   }
-  if (t < n_fast) {                               // n_fast is odd: t is even here
-    tile_header(t);
-    if (wave_live) {
-      step(s_a, s_b, &lds[0][1][0], &lds[1][0][0]);
+  static_assert(NS == 2 || NS == 4, "the fast loop is unrolled for rings of 2 or 4 slots");
+  {
+    const int t0 = t;                             // a multiple of NS: slots restart at 0
+    if (t < n_fast) { fast_iter(t, std::integral_constant<int, 0>{}); ++t; }
+    if (NS > 2) {
+      if (t < n_fast) { fast_iter(t, std::integral_constant<int, 1>{}); ++t; }
+      if (t < n_fast) { fast_iter(t, std::integral_constant<int, 2 % NS>{}); ++t; }
+    }
+    if (((t - t0) & 1) && wave_live) {            // an odd count left the scores in s_b
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) s_a[kb][rb] = s_b[kb][rb];
     }
-    ++t;
   }
   // Remaining tiles (the causal diagonal and the end of the sequence), one at
   // a time without overlap; s_a holds the scores of tile t.
   for (; t < nt; ++t) {
     const int key0 = kv_begin + t * BN;
-    tile_header(t);
-    unsigned char *v_cur = &lds[1][t & 1][0];
+    arrive();
+    issue_copies((t + NS - 1) % NS, t % NS, t);
+    const uint32_t v_cur = v_slot(t);
     if (key0 + BN > T) {
       // Slots past the end of the sequence hold whatever the pool held: clear
       // those V rows so that 0 * garbage cannot poison the products.
       for (int c = tid; c < BN * CPR; c += NT)
-        if (key0 + c / CPR >= T) *reinterpret_cast<u32x4 *>(v_cur + c * 16) = u32x4{0u, 0u, 0u, 0u};
+        if (key0 + c / CPR >= T) *reinterpret_cast<u32x4 *>(lds + v_cur + c * 16) = u32x4{0u, 0u, 0u, 0u};
       __syncthreads();
     }
     if (t < my_nt) {
       tail_step(s_a, v_cur);
       if (t + 1 < my_nt)
-        plain_scores(s_a, &lds[0][(t + 1) & 1][0], key0 + BN, key0 + 2 * BN - 1 > lo_limit);
+        plain_scores(s_a, k_slot(t + 1), key0 + BN, key0 + 2 * BN - 1 > lo_limit);
     }
   }
+  wait_pending(std::integral_constant<int, 0>{});   // let the unused trailing copies drain
 
   // ---- epilogue
 #pragma unroll
@@ -655,26 +711,35 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(
   *reinterpret_cast<bf16x4 *>(op) = o4;
 }
 
-template <int D, int RB, int NW, int WPE>
+template <int D, int RB, int NW, int WPE, int NS>
 static int launch_attn_t(const LaunchParams &p, hipStream_t st) {
-  hipLaunchKernelGGL((prefill_attn_kernel<D, RB, NW, WPE>), dim3((unsigned)p.num_items), dim3(NW * 64), 0,
-                     st, (const __bf16 *)p.q, (const __bf16 *)p.k_pool, (const __bf16 *)p.v_pool,
+  constexpr size_t lds_bytes = (size_t)2 * NS * kTileKeys * D * 2;
+  auto kernel = prefill_attn_kernel<D, RB, NW, WPE, NS>;
+  static const hipError_t attr = hipFuncSetAttribute(
+      (const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (attr != hipSuccess) return (int)attr;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)p.num_items), dim3(NW * 64), lds_bytes, st,
+                     (const __bf16 *)p.q, (const __bf16 *)p.k_pool, (const __bf16 *)p.v_pool,
                      p.block_table, (__bf16 *)p.out, p.partials, p.items, p.Hq, p.Hkv, p.max_blocks,
                      p.scale_log2e);
   return (int)hipGetLastError();
 }
 
+// Tile shapes: 64 and 128 query rows run two workgroups per CU with two-slot
+// rings (64 KB at d=128); 256 rows run one eight-wave workgroup per CU that
+// shares every K/V tile among twice as many rows and spends 128 of the 160 KB
+// of LDS on four-slot rings.
 int launch_attention(const LaunchParams &p, void *stream) {
   if (p.num_items == 0) return 0;
   hipStream_t st = (hipStream_t)stream;
   if (p.d == 128) {
-    if (p.tile_rows == 64) return launch_attn_t<128, 1, 2, 2>(p, st);
-    if (p.tile_rows == 128) return launch_attn_t<128, 1, 4, 2>(p, st);
-    return launch_attn_t<128, 1, 8, 2>(p, st);
+    if (p.tile_rows == 64) return launch_attn_t<128, 1, 2, 2, 2>(p, st);
+    if (p.tile_rows == 128) return launch_attn_t<128, 1, 4, 2, 2>(p, st);
+    return launch_attn_t<128, 1, 8, 2, 4>(p, st);
   }
-  if (p.tile_rows == 64) return launch_attn_t<64, 1, 2, 2>(p, st);
-  if (p.tile_rows == 128) return launch_attn_t<64, 1, 4, 2>(p, st);
-  return launch_attn_t<64, 1, 8, 2>(p, st);
+  if (p.tile_rows == 64) return launch_attn_t<64, 1, 2, 2, 2>(p, st);
+  if (p.tile_rows == 128) return launch_attn_t<64, 1, 4, 2, 2>(p, st);
+  return launch_attn_t<64, 1, 8, 2, 4>(p, st);
 }
 
 int launch_reduce(const LaunchParams &p, void *stream) {
