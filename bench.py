@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--split-kv", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-placement-hint", action="store_true",
+                    help="do not give the planner the host block table (no prefix-sharing placement)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB (read + write), for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -117,7 +119,8 @@ def main():
     bt = torch.from_numpy(b.block_table).cuda()
     out = torch.empty_like(t["q"])
     t0 = time.perf_counter()
-    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, tile_rows=args.tile_rows, split_kv=args.split_kv)
+    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, tile_rows=args.tile_rows, split_kv=args.split_kv,
+                  block_table=None if args.no_placement_hint else b.block_table)
     plan_ms = (time.perf_counter() - t0) * 1e3
     info = plan.prism_plan_get_info()
     assert info.flops == acc["flops"]

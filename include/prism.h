@@ -84,6 +84,12 @@ typedef struct prism_plan_options {
   int32_t split_kv;            /* 0 auto, 1 never split, n>1 force n-way split         */
   int32_t min_split_keys;      /* auto split: smallest KV chunk, multiple of 64        */
   int32_t reserved[5];
+  /* Optional HOST copy of the block table (int32 [batch][max_blocks_per_req]),
+   * read only during plan creation.  Requests whose tables start with the same
+   * page share a cached prefix (exact-prefix reuse, Eq. 3); the planner then
+   * runs their workgroups next to each other on one die so that the shared
+   * pages are fetched from HBM once.  NULL = no placement hint.                */
+  const int32_t *block_table_host;
 } prism_plan_options_t;
 
 typedef struct prism_plan prism_plan_t;

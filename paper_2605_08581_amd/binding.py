@@ -46,7 +46,8 @@ class Shape(ctypes.Structure):
 
 class PlanOptions(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("split_kv", ctypes.c_int32),
-                ("min_split_keys", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+                ("min_split_keys", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5),
+                ("block_table_host", ctypes.c_void_p)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -139,12 +140,22 @@ def prism_validate(shape: Shape, prefix_len, suffix_len, block_table) -> int:
     return int(load().prism_validate(ctypes.byref(shape), pl.ctypes.data, sl.ctypes.data, bt.ctypes.data))
 
 
+def _options(tile_rows, split_kv, min_split_keys, block_table):
+    """PlanOptions plus the host array it points to (keep both alive during the call)."""
+    opt = PlanOptions(tile_rows, split_kv, min_split_keys)
+    bt = None
+    if block_table is not None:
+        bt = _host_i32(block_table)
+        opt.block_table_host = bt.ctypes.data
+    return opt, bt
+
+
 def prism_plan_dry_run(shape: Shape, prefix_len, suffix_len, tile_rows: int = 0, split_kv: int = 0,
-                       min_split_keys: int = 0):
+                       min_split_keys: int = 0, block_table=None):
     """Host-only schedule: returns (PlanInfo, workspace_bytes, items int32 [n, 8])."""
     lib = load()
     pl, sl = _host_i32(prefix_len), _host_i32(suffix_len)
-    opt = PlanOptions(tile_rows, split_kv, min_split_keys)
+    opt, _bt = _options(tile_rows, split_kv, min_split_keys, block_table)
     info, ws = PlanInfo(), ctypes.c_size_t()
     n = lib.prism_plan_dry_run(ctypes.byref(shape), pl.ctypes.data, sl.ctypes.data, ctypes.byref(opt),
                                ctypes.byref(info), ctypes.byref(ws), None, 0)
@@ -161,7 +172,7 @@ class Plan:
     """Owns a prism_plan_t*.  Methods are the C entry points of the same name."""
 
     def __init__(self, shape: Shape, prefix_len, suffix_len, tile_rows: int = 0, split_kv: int = 0,
-                 min_split_keys: int = 0):
+                 min_split_keys: int = 0, block_table=None):
         lib = load()
         self._lib = lib
         self._h = ctypes.c_void_p()
@@ -169,7 +180,7 @@ class Plan:
         pl, sl = _host_i32(prefix_len), _host_i32(suffix_len)
         if pl.shape != (shape.batch,) or sl.shape != (shape.batch,):
             raise ValueError("prefix_len/suffix_len must have `batch` entries")
-        opt = PlanOptions(tile_rows, split_kv, min_split_keys)
+        opt, _bt = _options(tile_rows, split_kv, min_split_keys, block_table)
         rc = lib.prism_plan_create(ctypes.byref(shape), pl.ctypes.data, sl.ctypes.data,
                                    ctypes.byref(opt), ctypes.byref(self._h))
         if rc != PRISM_OK:
@@ -177,9 +188,10 @@ class Plan:
             raise PrismError(rc, "prism_plan_create")
 
     def close(self):
-        if getattr(self, "_h", None) is not None and self._h:
-            self._lib.prism_plan_destroy(self._h)
-            self._h = ctypes.c_void_p()
+        h = getattr(self, "_h", None)
+        if h is not None and h.value and ctypes is not None:
+            self._lib.prism_plan_destroy(h)
+            self._h.value = None
 
     __del__ = close
 

@@ -35,6 +35,8 @@ struct RowTile {
   int kv_len;      // keys visible to the tile's last row
   int cost;        // key tiles
   int group_cost;  // cost of the heaviest row tile of the same (request, kv head)
+  int cluster;     // requests with a common cached prefix share a cluster
+  int64_t cluster_cost;   // all key tiles of the (cluster, kv head) set
 };
 
 }  // namespace
@@ -70,6 +72,20 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
   for (int r = 0; r < s.batch; ++r)
     for (int i = 0; i < suffix[r]; ++i) sch.toks.push_back(TokInfo{r, prefix[r] + i});
 
+  // Requests that share a cached prefix start with the same page: give them
+  // one cluster id (the smallest request index of the cluster).
+  std::vector<int> cluster(s.batch);
+  for (int r = 0; r < s.batch; ++r) cluster[r] = r;
+  if (opt.block_table_host) {
+    std::map<int32_t, int> first_page_owner;
+    for (int r = 0; r < s.batch; ++r) {
+      if (prefix[r] < kPage || suffix[r] == 0) continue;       // no whole cached page
+      const int32_t pg = opt.block_table_host[(size_t)r * s.max_blocks_per_req];
+      auto ins = first_page_owner.insert({pg, r});
+      cluster[r] = ins.first->second;
+    }
+  }
+
   // Row tiles of every (request, kv head).
   std::vector<RowTile> tiles;
   int64_t total_cost = 0;
@@ -84,7 +100,7 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
         const int kv_len = P + last_row / G + 1;
         const int cost = (kv_len + kTileKeys - 1) / kTileKeys;
         const int gmax = (P + S + kTileKeys - 1) / kTileKeys;
-        tiles.push_back(RowTile{r, h, t * tile_rows, kv_len, cost, gmax});
+        tiles.push_back(RowTile{r, h, t * tile_rows, kv_len, cost, gmax, cluster[r], 0});
         total_cost += cost;
       }
     }
@@ -96,20 +112,29 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
   const int64_t target_items = 3LL * kNumCU;
   int chunk = (int)std::max<int64_t>(min_chunk, (total_cost + target_items - 1) / target_items);
 
-  // Longest first; row tiles of one (request, kv head) stay adjacent so that
-  // they run at the same time and find each other's K/V pages in cache.
+  // Heaviest (cluster, kv head) set first; inside a set the requests, and
+  // inside a request the row tiles, stay adjacent so that they run at the same
+  // time and find each other's K/V pages in cache.
+  {
+    std::map<std::pair<int, int>, int64_t> set_cost;
+    for (const RowTile &t : tiles) set_cost[{t.cluster, t.kv_head}] += t.cost;
+    for (RowTile &t : tiles) t.cluster_cost = set_cost[{t.cluster, t.kv_head}];
+  }
   std::stable_sort(tiles.begin(), tiles.end(), [](const RowTile &a, const RowTile &b) {
+    if (a.cluster_cost != b.cluster_cost) return a.cluster_cost > b.cluster_cost;
+    if (a.cluster != b.cluster) return a.cluster < b.cluster;
+    if (a.kv_head != b.kv_head) return a.kv_head < b.kv_head;
     if (a.group_cost != b.group_cost) return a.group_cost > b.group_cost;
     if (a.req != b.req) return a.req < b.req;
-    if (a.kv_head != b.kv_head) return a.kv_head < b.kv_head;
     return a.row0 > b.row0;
   });
 
   // Workgroup b runs on accelerator die b % 8, and each die has its own L2.
-  // Row tiles (and key chunks) of one (request, kv head) read the same K/V
-  // pages, so each such group is dealt whole to one die - the least loaded so
-  // far, heaviest groups first - and the per-die lists are then interleaved
-  // so that list position k of die x becomes workgroup 8k + x.
+  // Row tiles (and key chunks) of one (request, kv head), and of requests with
+  // a common cached prefix, read the same K/V pages, so each (cluster, kv
+  // head) set is dealt whole to one die - the least loaded so far, heaviest
+  // sets first - and the per-die lists are then interleaved so that list
+  // position k of die x becomes workgroup 8k + x.
   std::vector<AttnItem> per_die[kNumXCD];
   int64_t die_load[kNumXCD] = {0};
   int next_slot = 0;
@@ -117,7 +142,7 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
   while (i < tiles.size()) {
     size_t j = i;
     int64_t group_cost = 0;
-    while (j < tiles.size() && tiles[j].req == tiles[i].req && tiles[j].kv_head == tiles[i].kv_head)
+    while (j < tiles.size() && tiles[j].cluster == tiles[i].cluster && tiles[j].kv_head == tiles[i].kv_head)
       group_cost += tiles[j++].cost;
     int die = 0;
     for (int x = 1; x < kNumXCD; ++x)

@@ -15,7 +15,7 @@ MAX_ABS, MEAN_ABS, NORM = 2e-2, 2e-3, 2e-2
 def run_hip(b, t, entry="prefill", **opts):
     """Run on cuda:0.  t: dict of device tensors (pools are modified in place)."""
     sh = B.shape_of(b)
-    plan = B.Plan(sh, b.prefix_len, b.suffix_len, **opts)
+    plan = B.Plan(sh, b.prefix_len, b.suffix_len, block_table=b.block_table, **opts)
     bt = torch.from_numpy(b.block_table).to("cuda")
     out = torch.full_like(t["q"], float("nan"))
     nws = plan.prism_plan_workspace_bytes()

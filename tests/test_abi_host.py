@@ -124,6 +124,24 @@ def test_planner_forced_and_disabled_split(lib):
     assert _check_cover(W.make_config(2), 0, 0).num_reduce_groups == 0
 
 
+def test_placement_hint_keeps_prefix_sharers_on_one_die(lib):
+    """With a host block table, requests whose tables start with the same page
+    (a common cached prefix) run the same kv head on the same die."""
+    b = W.make_config(2)
+    sh = B.shape_of(b)
+    _, _, items = B.prism_plan_dry_run(sh, b.prefix_len, b.suffix_len, block_table=b.block_table)
+    _, _, plain = B.prism_plan_dry_run(sh, b.prefix_len, b.suffix_len)
+    key = lambda it: tuple(sorted(map(tuple, it[it[:, 0] >= 0][:, :6].tolist())))
+    assert key(items) == key(plain), "the hint may only reorder the work"
+    first = {r: int(b.block_table[r, 0]) for r in range(b.batch) if b.prefix_len[r] >= 16}
+    die = {}
+    for pos, (req, kvh, *_rest) in enumerate(items.tolist()):
+        if req >= 0 and req in first:
+            die.setdefault((first[req], kvh), set()).add(pos % 8)
+    assert len({k[0] for k in die}) < len(first), "the Zipf wave has requests with a common prefix"
+    assert all(len(v) == 1 for v in die.values())
+
+
 def test_validate_flags_bad_tables(lib):
     b = W.make_custom_batch("t", W.Geometry(4, 2, 64), [32, 32, 5], [20, 9, 30], seed=2,
                             share_groups=[0, 0, -1])
