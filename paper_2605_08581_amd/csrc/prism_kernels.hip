@@ -445,8 +445,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   constexpr int NEL = KB * 16;                    // score elements per lane per row block
   constexpr int LA = 3;                           // fragment reads run this many chunks ahead
   constexpr int CSPAN = NQK + (KS - 1) * DB;      // chunks over which the exponentials spread
-  auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], uint32_t k_next,
-                  uint32_t v_cur) __attribute__((always_inline)) {
+  auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], uint32_t k_next, uint32_t v_cur,
+                  int next_key0, auto mask_tag) __attribute__((always_inline)) {
     static_assert(RB == 1, "the overlapped step is written for one 32-row block per wave");
     const float mc = m_run[0] * scale_log2e;
     float sum = 0.f;
@@ -503,6 +503,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       if (c < NQK + NPV - DB) __builtin_amdgcn_sched_barrier(0);
     }
     l_run[0] += sum;
+    if (decltype(mask_tag)::value) mask_tile(sn, next_key0);   // the next tile touches the diagonal
     raise_max(sn);
   };
 
@@ -551,22 +552,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     wait_pending(std::integral_constant<int, PENDING_OK>{});   // this wave's part has landed
     __syncthreads();                              // everyone's has; the previous iteration is over
   };
-  auto fast_iter = [&](int t, auto j_tag) __attribute__((always_inline)) {
-    constexpr int j = decltype(j_tag)::value;
-    static_assert(NS % 2 == 0, "score buffers alternate with the tile parity");
-    arrive();
-    issue_copies((j + NS - 1) % NS, j, t);
-    if (wave_live) {
-      constexpr uint32_t k_next = (uint32_t)((j + 1) % NS) * TILE_BYTES;
-      constexpr uint32_t v_cur = (uint32_t)(NS + j) * TILE_BYTES;
-      if (j % 2 == 0) step(s_a, s_b, k_next, v_cur);
-      else step(s_b, s_a, k_next, v_cur);
-    }
-  };
-
   // Tiles 0 .. n_fast-1 are followed by a tile that no row of the workgroup
-  // needs masked: they run the overlapped step, NS per trip so that ring
-  // slots and score buffers are compile-time choices.
+  // needs masked.  They run NS per trip with j = t % NS a compile-time value,
+  // so that ring slots and the score buffer in use are fixed in the code and
+  // every LDS address is a register plus an immediate.
   int n_fast = 0;
   {
     const int blk_limit = P + it.row0 / G;        // last key visible to the workgroup's first row
@@ -574,49 +563,56 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     if (n_fast > nt - 1) n_fast = nt - 1;
     if (n_fast < 0) n_fast = 0;
   }
+  auto fast_iteration = [&](int t, auto j_tag) __attribute__((always_inline)) {
+    constexpr int j = decltype(j_tag)::value;
+    static_assert(NS % 2 == 0, "score buffers alternate with the tile parity");
+    constexpr uint32_t k_next = (uint32_t)((j + 1) % NS) * TILE_BYTES;
+    constexpr uint32_t v_cur = (uint32_t)(NS + j) * TILE_BYTES;
+    arrive();
+    issue_copies((j + NS - 1) % NS, j, t);
+    if (wave_live) {
+      if (j % 2 == 0) step(s_a, s_b, k_next, v_cur, 0, std::false_type{});
+      else step(s_b, s_a, k_next, v_cur, 0, std::false_type{});
+    }
+  };
+  static_assert(NS == 2 || NS == 4, "the loop is unrolled for rings of 2 or 4 slots");
   int t = 0;
   for (; t + NS <= n_fast; t += NS) {
-    fast_iter(t, std::integral_constant<int, 0>{});
-    fast_iter(t + 1, std::integral_constant<int, 1>{});
+    fast_iteration(t, std::integral_constant<int, 0>{});
+    fast_iteration(t + 1, std::integral_constant<int, 1>{});
     if (NS > 2) {
-      fast_iter(t + 2, std::integral_constant<int, 2 % NS>{});
-      fast_iter(t + 3, std::integral_constant<int, 3 % NS>{});
+      fast_iteration(t + 2, std::integral_constant<int, 2 % NS>{});
+      fast_iteration(t + 3, std::integral_constant<int, 3 % NS>{});
     }
   }
-  static_assert(NS == 2 || NS == 4, "the fast loop is unrolled for rings of 2 or 4 slots");
-  {
-    const int t0 = t;                             // a multiple of NS: slots restart at 0
-    if (t < n_fast) { fast_iter(t, std::integral_constant<int, 0>{}); ++t; }
-    if (NS > 2) {
-      if (t < n_fast) { fast_iter(t, std::integral_constant<int, 1>{}); ++t; }
-      if (t < n_fast) { fast_iter(t, std::integral_constant<int, 2 % NS>{}); ++t; }
-    }
-    if (((t - t0) & 1) && wave_live) {            // an odd count left the scores in s_b
+  // The tiles up to the causal diagonal (and a few left over from the loop
+  // above): the same overlapped step with the causal mask applied to the new
+  // scores, ring slots chosen at run time, scores handed back in s_a.  (A wave
+  // whose rows end early computes fully masked tiles until the workgroup's key
+  // range ends - at most two - and they add exact zeros.)
+  for (; t + 1 < nt; ++t) {
+    arrive();
+    issue_copies((t + NS - 1) % NS, t % NS, t);
+    if (wave_live) {
+      step(s_a, s_b, k_slot(t + 1), v_slot(t), kv_begin + (t + 1) * BN, std::true_type{});
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) s_a[kb][rb] = s_b[kb][rb];
     }
   }
-  // Remaining tiles (the causal diagonal and the end of the sequence), one at
-  // a time without overlap; s_a holds the scores of tile t.
-  for (; t < nt; ++t) {
-    const int key0 = kv_begin + t * BN;
-    arrive();
-    issue_copies((t + NS - 1) % NS, t % NS, t);
+  if (nt > 0) {                                   // the last tile: softmax and PV only
     const uint32_t v_cur = v_slot(t);
-    if (key0 + BN > T) {
+    arrive();
+    if (kv_begin + nt * BN > T) {
       // Slots past the end of the sequence hold whatever the pool held: clear
       // those V rows so that 0 * garbage cannot poison the products.
       for (int c = tid; c < BN * CPR; c += NT)
-        if (key0 + c / CPR >= T) *reinterpret_cast<u32x4 *>(lds + v_cur + c * 16) = u32x4{0u, 0u, 0u, 0u};
+        if (kv_begin + t * BN + c / CPR >= T)
+          *reinterpret_cast<u32x4 *>(lds + v_cur + c * 16) = u32x4{0u, 0u, 0u, 0u};
       __syncthreads();
     }
-    if (t < my_nt) {
-      tail_step(s_a, v_cur);
-      if (t + 1 < my_nt)
-        plain_scores(s_a, k_slot(t + 1), key0 + BN, key0 + 2 * BN - 1 > lo_limit);
-    }
+    if (wave_live) tail_step(s_a, v_cur);
   }
   wait_pending(std::integral_constant<int, 0>{});   // let the unused trailing copies drain
 
