@@ -175,3 +175,53 @@ def test_full_size_configs_sampled_rows(oracle_lib, index):
 @pytest.mark.parametrize("hit", [0.0, 0.5, 0.9])
 def test_hit_rate_sweep_sampled_rows(oracle_lib, hit):
     _sampled_parity(oracle_lib, W.make_hit_rate_batch(hit, batch=8), 600)
+
+
+def test_chunked_prefill_equals_one_shot(oracle_lib):
+    """Chunked prefill (the engine the paper builds on keeps it, Sec. 4.1): the
+    suffix is fed in fixed-size chunks, each chunk attending to the prefix, to
+    the chunks already appended, and to itself.  Chunk boundaries fall inside
+    pages, so later chunks see a partial private page as part of their prefix.
+    Pools must end bit-identical and outputs within tolerance of the oracle's
+    one-shot result."""
+    geom = W.Geometry(8, 2, 128)
+    b = W.make_custom_batch("chunked", geom, [48, 0, 200], [150, 333, 90], seed=21)
+    t = W.make_tensors(b, "cuda")
+    host = {k: W.bf16_bits(v) for k, v in t.items()}
+    one_shot, _ = run_hip(b, {k: v.clone() for k, v in t.items()})
+    chunk = 56                                   # not a multiple of the page size
+    offs = b.suffix_offsets
+    out = torch.full_like(t["q"], float("nan"))
+    bt = torch.from_numpy(b.block_table).cuda()
+    done = np.zeros(b.batch, dtype=np.int64)
+    while (done < b.suffix_len).any():
+        S = np.minimum(chunk, b.suffix_len - done).astype(np.int32)
+        P = (b.prefix_len + done).astype(np.int32)
+        rows = np.concatenate([np.arange(offs[r] + done[r], offs[r] + done[r] + S[r]) for r in range(b.batch)])
+        idx = torch.from_numpy(rows).cuda()
+        plan = B.Plan(B.shape_of(b), P, S, block_table=b.block_table)
+        n = plan.prism_plan_workspace_bytes()
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+        o = torch.empty((len(rows),) + tuple(t["q"].shape[1:]), dtype=t["q"].dtype, device="cuda")
+        plan.prism_prefix_prefill(t["q"][idx].contiguous(), t["k_suffix"][idx].contiguous(),
+                                  t["v_suffix"][idx].contiguous(), t["k_pool"], t["v_pool"], bt, o, ws)
+        torch.cuda.synchronize()
+        plan.close()
+        out[idx] = o
+        done += S
+    kp, vp = oracle_lib.kv_append(host["k_suffix"], host["v_suffix"], host["k_pool"], host["v_pool"],
+                                  b.block_table, b.prefix_len, b.suffix_len)
+    assert np.array_equal(W.bf16_bits(t["k_pool"]), kp) and np.array_equal(W.bf16_bits(t["v_pool"]), vp)
+    ref = oracle_lib.attention(host["q"], kp, vp, b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale)
+    check_close(widen(W.bf16_bits(out)), ref, "chunked")
+    dmax = float((out.double() - one_shot.double()).abs().max())
+    assert dmax <= 2.0 ** -7 * float(one_shot.double().abs().max())
+
+
+@pytest.mark.parametrize("geom", [W.Geometry(40, 40, 128), W.Geometry(32, 8, 128)], ids=["mha", "gqa"])
+def test_single_token_suffix_decode_shape(oracle_lib, geom):
+    """One uncached token per request over a long cached prefix (the first
+    decode step after prefill, the T_1tok term of Eq. 2)."""
+    b = W.make_custom_batch("decode", geom, [1000, 37, 4096, 16], [1, 1, 1, 1], seed=22)
+    full_parity(oracle_lib, b)
+    full_parity(oracle_lib, b, split_kv=4)
