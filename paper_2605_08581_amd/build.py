@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprism.so")
-SOURCES = ["prism_plan.cpp", "prism_api.cpp", "prism_kernels.hip"]
+SOURCES = ["prism_plan.cpp", "prism_api.cpp", "prism_sched.cpp", "prism_kernels.hip"]
 # packed fp32 VALU ops stay off: the kernels are written as ordinary float code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -23,10 +23,15 @@ def lib():
 
 
 def test_library_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "prism.h")).read()
-    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(prism_[a-z_]+)\s*\(", body))
-    assert declared == set(B.EXPORTS)
+    from paper_2605_08581_amd import sched as S
+    declared = set()
+    for name, exports in (("prism.h", B.EXPORTS), ("prism_sched.h", S.EXPORTS)):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        found = set(re.findall(r"\b(prism_[a-z_]+)\s*\(", body))
+        assert found == set(exports), name
+        declared |= found
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["prism.h", "prism_sched.h"]
     for name in declared:
         assert hasattr(lib, name), name
     assert B.prism_version() == 100

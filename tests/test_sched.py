@@ -1,0 +1,468 @@
+"""Host control plane (QAS scheduler, DART radix tree): the C++ library against a
+hand-worked round, a plain-Python reference written from the paper, brute-force
+prefix matching, and the invariants of Alg. 1 / Alg. 2.  No GPU."""
+import os
+import random
+
+import numpy as np
+import pytest
+
+from oracle import control_plane as ref
+from paper_2605_08581_amd import binding as B
+from paper_2605_08581_amd import sched as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PAGE = 16
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2605_08581_amd import build
+        build.build()
+    return B.load()
+
+
+# ------------------------------------------------------------------- QAS ----
+
+def _golden():
+    g = {"pending": {}, "star": {}, "signature": {}, "score": {}, "p_hat": {}, "offsets": {}}
+    for line in open(os.path.join(ROOT, "tests", "golden", "qas_worked_example.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        key, val = line.split(":")
+        parts = key.split()
+        nums = val.split()
+        if len(parts) == 2:
+            g[parts[0]][int(parts[1])] = [float(x) if "." in x else int(x) for x in nums]
+        else:
+            g[parts[0]] = [int(x) for x in nums]
+    return g
+
+
+def _run_round(q: S.Qas):
+    hints, segs, (pri, npri) = q.round()
+    out = dict(dispatch=[h.request for h in hints], lane=[h.lane for h in hints], rank=[h.rank for h in hints],
+               bucket_order=[h.bucket_order for h in hints], score=[h.bucket_score for h in hints],
+               bucket=[h.bucket for h in hints],
+               star=[[s.segment for s in segs[h.first:h.first + h.num_segments]] for h in hints],
+               offsets=[[s.end_offset for s in segs[h.first:h.first + h.num_segments]] for h in hints],
+               seg_prio=[[s.priority for s in segs[h.first:h.first + h.num_segments]] for h in hints],
+               seg_cnt=[[(s.g, s.a, s.n) for s in segs[h.first:h.first + h.num_segments]] for h in hints],
+               p_hat={pri[i].segment: pri[i].priority for i in range(npri)},
+               counters={pri[i].segment: (pri[i].g, pri[i].a, pri[i].n) for i in range(npri)})
+    return out
+
+
+def test_qas_worked_example():
+    g = _golden()
+    q = S.Qas(dispatch_budget=4, cold_quota=1)
+    q.submit(100, 0.0, [7], [128])
+    assert q.round()[0][0].request == 100  # now active with skeleton [7]
+    for i in sorted(g["pending"]):
+        q.submit(i, 1.0 + i, g["pending"][i], [128] * len(g["pending"][i]), system_tokens=10, suffix_tokens=5)
+    r = _run_round(q)
+    assert r["dispatch"] == g["dispatch"]
+    assert r["lane"] == g["lane"]
+    for i, rid in enumerate(r["dispatch"]):
+        assert r["star"][i] == g["star"][rid]
+        sig = g["signature"][rid][0]
+        assert r["score"][i] == pytest.approx(g["score"][sig][0], rel=1e-12)
+        assert r["bucket_order"][i] == g["bucket_order"].index(sig)
+    assert r["offsets"][0] == g["offsets"][0]
+    for seg, val in g["p_hat"].items():
+        assert r["p_hat"][seg] == val[0]
+    assert q.pending == len(g["left_pending"]) and q.active == 1 + len(g["dispatch"])
+    # the reference agrees with the hand-worked round too
+    rr = ref.qas_round([dict(id=i, skel=g["pending"][i]) for i in sorted(g["pending"])], [[7]], M=4, q_cold=1)
+    assert rr["dispatch"] == g["dispatch"] and rr["lane"] == g["lane"]
+    assert [rr["star"][i] for i in range(4)] == [g["star"][rid] for rid in g["dispatch"]]
+    assert rr["score"][0] == pytest.approx(g["score"][7][0], rel=1e-12)
+    assert {k: v for k, v in rr["p_hat"].items()} == {k: float(v[0]) for k, v in g["p_hat"].items()}
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_qas_matches_reference_over_many_rounds(seed):
+    rng = random.Random(seed)
+    M = rng.choice([1, 2, 4, 8])
+    q_cold = rng.choice([0, 1, 2, M])
+    q_cold = min(q_cold, M)
+    f_front = rng.choice([-1, 1, 2, 3])
+    kappa = rng.choice([1, 2])
+    q = S.Qas(M, cold_quota=q_cold, front_width=f_front, signature_size=kappa)
+    universe = list(range(rng.choice([4, 9, 30])))
+    pending, active, next_id = [], {}, 0
+    for rnd in range(8):
+        for _ in range(rng.randint(0, 10)):
+            m = rng.randint(0, 5)
+            skel = [rng.choice(universe) for _ in range(m)] if rng.random() < 0.3 else rng.sample(universe, min(m, len(universe)))
+            ro = [rng.random() < 0.8 for _ in skel] if rng.random() < 0.5 else None
+            lens = [rng.randint(1, 200) for _ in skel]
+            q.submit(next_id, float(next_id), skel, lens, ro, system_tokens=7, suffix_tokens=3)
+            pending.append(dict(id=next_id, skel=skel, reorderable=ro, lens=lens))
+            next_id += 1
+        for rid in [r for r in active if rng.random() < 0.4]:
+            q.complete(rid)
+            del active[rid]
+        want = ref.qas_round(pending, list(active.values()), M=M, q_cold=q_cold, f_front=max(f_front, 0), kappa=kappa)
+        got = _run_round(q)
+        assert got["dispatch"] == want["dispatch"]
+        assert got["lane"] == want["lane"]
+        assert got["star"] == want["star"]
+        assert got["rank"] == want["rank"]
+        assert got["bucket_order"] == want["bucket_order"]
+        assert got["score"] == pytest.approx(want["score"], rel=1e-12)
+        assert got["p_hat"] == pytest.approx(want["p_hat"], rel=1e-12)
+        for seg, (g_, a_, n_) in got["counters"].items():
+            assert (g_, a_, n_) == (want["g"].get(seg, 0), want["a"].get(seg, 0), want["n"].get(seg, 0))
+        # same signature <=> same bucket hash within the round
+        sig_of = {}
+        for b, s in zip(got["bucket"], want["signature"]):
+            assert sig_of.setdefault(b, s) == s
+        # Alg. 1 invariants
+        assert len(got["dispatch"]) == min(M, len(pending))
+        assert sum(got["lane"]) <= q_cold
+        ids = [p["id"] for p in pending]
+        hot = [r for r, l in zip(got["dispatch"], got["lane"]) if l == 0]
+        cold = [r for r, l in zip(got["dispatch"], got["lane"]) if l == 1]
+        assert cold == [i for i in ids if i not in hot][:len(cold)]  # oldest unselected, FIFO
+        by_id = {p["id"]: p for p in pending}
+        for rid, star, offs in zip(got["dispatch"], got["star"], got["offsets"]):
+            p = by_id[rid]
+            assert sorted(star) == sorted(p["skel"])
+            ro = p["reorderable"] or [True] * len(star)
+            for j, fixed in enumerate(ro):
+                if not fixed:
+                    assert star[j] == p["skel"][j]  # pinned segments stay where they were
+            if offs:
+                assert offs[-1] == 7 + sum(p["lens"])
+            if len(set(p["skel"])) == len(p["skel"]):  # lengths follow their segments
+                length = dict(zip(p["skel"], p["lens"]))
+                assert offs == list(7 + np.cumsum([length[s] for s in star]))
+            active[rid] = p["skel"]
+        pending = [p for p in pending if p["id"] not in got["dispatch"]]
+        assert q.pending == len(pending) and q.active == len(active)
+
+
+def test_qas_fifo_mode_and_errors():
+    q = S.Qas(3, mode=S.QAS_MODE_FIFO)
+    for i in range(5):
+        q.submit(i, i, [9 - i, 1], [10, 20])
+    r = _run_round(q)
+    assert r["dispatch"] == [0, 1, 2] and r["star"][0] == [9, 1]
+    assert _run_round(q)["dispatch"] == [3, 4]
+    with pytest.raises(B.PrismError):
+        q.submit(0, 0.0, [1], [1])      # id still active
+    q.complete(0)
+    q.submit(0, 0.0, [1], [1])
+    with pytest.raises(B.PrismError):
+        q.complete(77)
+    with pytest.raises(B.PrismError):
+        S.Qas(0)
+    with pytest.raises(B.PrismError):
+        q.submit(50, 0.0, [-1], [1])
+
+
+def test_qas_cold_lane_prevents_starvation():
+    """A rare-prefix request is admitted within ceil(position / q_cold) rounds
+    even if hot buckets keep arriving (Sec. 3.2, cold lane)."""
+    q = S.Qas(4, cold_quota=1)
+    q.submit(0, 0.0, [99], [128])
+    rounds, nid, seen = 0, 1, False
+    while not seen and rounds < 10:
+        for _ in range(6):
+            q.submit(nid, float(nid), [1, 2], [128, 128])
+            nid += 1
+        r = _run_round(q)
+        seen = 0 in r["dispatch"]
+        if seen:
+            assert r["lane"][r["dispatch"].index(0)] == 1
+        rounds += 1
+    assert seen and rounds == 1
+    q0 = S.Qas(4, cold_quota=0)
+    q0.submit(0, 0.0, [99], [128])
+    for rounds in range(5):
+        for _ in range(6):
+            q0.submit(nid, float(nid), [1, 2], [128, 128])
+            nid += 1
+        assert 0 not in _run_round(q0)["dispatch"]  # starves without the cold lane
+
+
+# ------------------------------------------------------------------ DART ----
+
+def _prompt(rng, segs, lib, sys_tokens, suffix_len):
+    toks = list(sys_tokens)
+    anchors = [(len(toks), S.SPAN_SYSTEM, -1)]
+    for s in segs:
+        toks += lib[s]
+        anchors.append((len(toks), S.SPAN_REUSABLE, s))
+    toks += [rng.randrange(32000) for _ in range(suffix_len)]
+    anchors.append((len(toks), S.SPAN_PRIVATE, -1))
+    return toks, anchors
+
+
+def _seg_lib(rng, n, lens=(16, 24, 40, 128)):
+    return {s: [rng.randrange(32000) for _ in range(rng.choice(lens))] for s in range(n)}
+
+
+def _dump(d: S.Dart):
+    return [dict(id=n.id, parent=n.parent, num_pages=n.num_pages, ref=n.ref, kind=n.kind, segment=n.segment,
+                 num_children=n.num_children, protected=n.is_protected, hits=n.hits, last=n.last,
+                 priority=n.priority, end_offset=n.end_offset) for n in d.dump()]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_dart_hits_equal_brute_force_without_pressure(seed):
+    rng = random.Random(seed)
+    lib = _seg_lib(rng, 6)
+    sys_t = [rng.randrange(32000) for _ in range(rng.choice([0, 5, 16, 33]))]
+    d = S.Dart(num_pages=20000)
+    published, live = [], []
+    for rid in range(60):
+        d.set_time(float(rid))
+        segs = [rng.randrange(6) for _ in range(rng.randint(0, 4))]
+        toks, anchors = _prompt(rng, segs, lib, sys_t, rng.randint(1, 40))
+        if rng.random() < 0.3:
+            anchors = []  # a request that exports no hints
+        assert d.peek(toks) == ref.hit_length(toks, published)
+        hit, row = d.admit(rid, toks, anchors, reserve_tokens=rng.choice([0, 32]))
+        assert hit == ref.hit_length(toks, published)
+        assert len(set(row.tolist())) == len(row) and row.min() >= 0
+        d.check()
+        row2 = d.commit(rid, row.copy())
+        assert (row2[:hit // PAGE] == row[:hit // PAGE]).all()
+        published.append(toks)
+        live.append(rid)
+        d.check()
+        if rng.random() < 0.5:
+            d.release(live.pop(rng.randrange(len(live))))
+            d.check()
+        # every node ends on a page boundary that some anchor or divergence fixed
+        for n in _dump(d):
+            assert n["end_offset"] % PAGE == 0 and n["num_pages"] >= 1
+    st = d.stats()
+    assert st.evicted_pages == 0 and st.admitted_requests == 60
+    assert st.free_pages + st.tree_pages + st.private_pages == st.num_pages
+
+
+def test_dart_same_wave_duplicates_are_merged_at_commit():
+    rng = random.Random(1)
+    lib = _seg_lib(rng, 2, lens=(64,))
+    toks, anchors = _prompt(rng, [0, 1], lib, [], 20)
+    d = S.Dart(num_pages=100)
+    h1, r1 = d.admit(1, toks, anchors)
+    h2, r2 = d.admit(2, toks, anchors)   # same wave: nothing published yet
+    assert h1 == 0 and h2 == 0 and not set(r1.tolist()) & set(r2.tolist())
+    free_before = d.stats().free_pages
+    d.commit(1, r1)
+    d.commit(2, r2)
+    full = len(toks) // PAGE
+    assert (r2[:full] == r1[:full]).all()           # re-pointed at the published pages
+    assert d.stats().free_pages == free_before + full
+    d.check()
+    d.release(1)
+    d.release(2)
+    d.check()
+    assert d.peek(toks) == ((len(toks) - 1) // PAGE) * PAGE
+
+
+def test_dart_splits_existing_edge_at_anchor():
+    rng = random.Random(2)
+    lib = _seg_lib(rng, 3, lens=(48,))
+    toks, anchors = _prompt(rng, [0, 1, 2], lib, [], 16)
+    d = S.Dart(num_pages=100)
+    _, r = d.admit(1, toks, [])          # no hints: one long unlabelled edge
+    d.commit(1, r)
+    assert len(d.dump()) == 1 and d.dump()[0].kind == S.SPAN_NONE
+    _, r = d.admit(2, toks, anchors)
+    d.commit(2, r)
+    nodes = sorted(_dump(d), key=lambda n: n["end_offset"])
+    assert [n["end_offset"] for n in nodes] == [48, 96, 144, 160]
+    assert [n["kind"] for n in nodes] == [S.SPAN_REUSABLE] * 3 + [S.SPAN_PRIVATE]
+    assert [n["segment"] for n in nodes] == [0, 1, 2, -1]
+    d.check()
+
+
+def _populate(rng, d, n_req, lib, sys_t, t0=0.0, release=0.8, reserve=0):
+    live = []
+    for rid in range(n_req):
+        d.set_time(t0 + rid)
+        segs = rng.sample(sorted(lib), rng.randint(1, 4))
+        toks, anchors = _prompt(rng, segs, lib, sys_t, rng.randint(1, 60))
+        _, row = d.admit(1000 + rid, toks, anchors, reserve_tokens=reserve)
+        d.commit(1000 + rid, row)
+        live.append(1000 + rid)
+        if rng.random() < release:
+            d.release(live.pop(rng.randrange(len(live))))
+    return live
+
+
+@pytest.mark.parametrize("policy", ["dart", "lru", "lru_active", "lfu"])
+@pytest.mark.parametrize("seed", range(4))
+def test_eviction_order_matches_reference(policy, seed):
+    rng = random.Random(100 + seed)
+    lib = _seg_lib(rng, 8)
+    sys_t = [rng.randrange(32000) for _ in range(20)]
+    f = rng.choice([-1, 2, 5])
+    d = S.Dart(num_pages=20000, policy=S.POLICIES[policy], protect_budget=f)
+    live = _populate(rng, d, 40, lib, sys_t)
+    table = [(s, rng.randint(0, 3), rng.choice([0, 0, 1, 2]), rng.choice([0, 0, 1]), 0.0) for s in rng.sample(sorted(lib), 5)]
+    table = [(s, g, a, n, 1.0 * g + 1e6 * a + 1e5 * n) for (s, g, a, n, _) in table]
+    d.set_round(100.0, table)
+    nodes = _dump(d)
+    active = {s: a for (s, g, a, n, p) in table}
+    want = ref.eviction_order(nodes, 10 ** 9, policy, f=max(f, 0), active_count=active)
+    assert want, "nothing evictable: the case is vacuous"
+    # evict in several calls so that a heap with leftovers is exercised too
+    got, k = [], 0
+    while True:
+        n_ev, freed = d.evict(rng.choice([1, 16, 200]))
+        log = d.evicted_log()
+        assert len(log) == n_ev
+        if n_ev == 0:
+            break
+        got += log
+        d.check()
+        k += 1
+    assert got == want
+    # locked and system nodes survive, and whatever survives is reachable
+    left = {n["id"] for n in _dump(d)}
+    for n in nodes:
+        if n["ref"] > 0 or n["kind"] == S.SPAN_SYSTEM:
+            assert n["id"] in left
+    if policy == "dart":
+        prot = ref.protection_set(nodes, max(f, 0))
+        assert {n["id"] for n in nodes if n["protected"]} == prot
+        assert len(prot) <= max(f, 0)
+    for rid in live:
+        d.release(rid)
+    d.check()
+
+
+def test_eviction_revalidates_stale_keys():
+    """Keys stored in the heap go stale when a node is used again; Alg. 2 must
+    notice at pop time and still evict in current-key order."""
+    rng = random.Random(7)
+    lib = _seg_lib(rng, 6, lens=(32,))
+    d = S.Dart(num_pages=20000, policy=S.EVICT_LRU)
+    prompts = []
+    for rid in range(12):
+        d.set_time(float(rid))
+        toks, anchors = _prompt(rng, [rid % 6], lib, [], 40 + rid)
+        _, row = d.admit(rid, toks, anchors)
+        d.commit(rid, row)
+        d.release(rid)                      # pushes the now-evictable leaf with its key
+        prompts.append((toks, anchors))
+    # touch the oldest leaves again: their heap entries are now too small
+    for rid in range(4):
+        d.set_time(100.0 + rid)
+        toks, anchors = prompts[rid]
+        hit, row = d.admit(100 + rid, toks + [1, 2, 3], anchors[:-1])
+        assert hit > 0
+        d.release(100 + rid)
+    nodes = _dump(d)
+    want = ref.eviction_order(nodes, 10 ** 9, "lru")
+    n_ev, _ = d.evict(10 ** 8)
+    assert d.evicted_log() == want and n_ev == len(want)
+    st = d.stats()
+    assert st.heap_stale > 0
+    assert st.tree_pages == 0 and st.free_pages == st.num_pages
+
+
+def test_dart_without_hints_orders_like_lru():
+    rng = random.Random(9)
+    orders = []
+    for policy in (S.EVICT_DART, S.EVICT_LRU):
+        rng = random.Random(9)
+        d = S.Dart(num_pages=5000, policy=policy)
+        for rid in range(30):
+            d.set_time(float(rid))
+            toks = [rng.randrange(50) for _ in range(rng.randint(17, 90))]
+            _, row = d.admit(rid, toks, [])
+            d.commit(rid, row)
+            d.release(rid)
+        d.evict(10 ** 8)
+        orders.append(d.evicted_log())
+    assert orders[0] == orders[1] and len(orders[0]) > 10
+
+
+def test_dart_eviction_prefers_private_then_low_priority_then_protected():
+    """Eq. 13 on a hand-built tree: three requests, one segment each, plus
+    private suffixes; priorities make segment 2 the one to keep."""
+    rng = random.Random(11)
+    lib = _seg_lib(rng, 3, lens=(32,))
+    d = S.Dart(num_pages=1000, protect_budget=1)
+    for rid, seg in enumerate([0, 1, 2]):
+        d.set_time(float(rid))
+        toks, anchors = _prompt(rng, [seg], lib, [], 33)
+        _, row = d.admit(rid, toks, anchors)
+        d.commit(rid, row)
+        d.release(rid)
+    # segment 0 has the oldest access but the highest priority: with f = 1 it is
+    # the protected anchor; segments 1 and 2 are unprotected and go by priority.
+    d.set_round(10.0, [(0, 5, 1, 0, 5 + 1e6), (1, 1, 0, 0, 1.0), (2, 3, 0, 0, 3.0)])
+    nodes = {n["id"]: n for n in _dump(d)}
+    d.evict(10 ** 8)
+    order = d.evicted_log()
+    kinds = [(nodes[i]["kind"], nodes[i]["segment"]) for i in order]
+    assert kinds == [(S.SPAN_PRIVATE, -1)] * 3 + [(S.SPAN_REUSABLE, 1), (S.SPAN_REUSABLE, 2), (S.SPAN_REUSABLE, 0)]
+    # private suffixes went in order of last access
+    assert [nodes[i]["last"] for i in order[:3]] == sorted(nodes[i]["last"] for i in order[:3])
+
+
+def test_dart_pressure_and_errors():
+    rng = random.Random(3)
+    lib = _seg_lib(rng, 4, lens=(64,))
+    d = S.Dart(num_pages=40)
+    toks, anchors = _prompt(rng, [0, 1], lib, [], 30)       # 158 tokens -> 10 pages
+    _, r1 = d.admit(1, toks, anchors)
+    d.commit(1, r1)
+    toks2, anchors2 = _prompt(rng, [2, 3], lib, [], 30)
+    _, r2 = d.admit(2, toks2, anchors2, reserve_tokens=32)   # 12 pages
+    toks3, anchors3 = _prompt(rng, [3, 2], lib, [], 200)     # 21 pages: does not fit while 1, 2 are locked
+    with pytest.raises(B.PrismError) as e:
+        d.admit(3, toks3, anchors3)
+    assert e.value.code == B.ERR_NO_MEMORY
+    d.check()
+    d.release(1)                                            # request 1's pages become evictable
+    hit, r3 = d.admit(3, toks3, anchors3)
+    assert hit == 0 and d.stats().evicted_pages > 0
+    assert not set(r3.tolist()) & set(r2.tolist())
+    d.check()
+    with pytest.raises(B.PrismError):
+        d.admit(3, toks3, anchors3)                          # duplicate id
+    with pytest.raises(B.PrismError):
+        d.commit(99, r3)
+    with pytest.raises(B.PrismError):
+        d.release(99)
+    with pytest.raises(B.PrismError):
+        d.admit(4, toks, [(5, S.SPAN_PRIVATE, -1), (3, S.SPAN_PRIVATE, -1)])  # anchors out of order
+    with pytest.raises(B.PrismError):
+        S.Dart(num_pages=0)
+    d.commit(3, r3)
+    d.release(2)
+    d.release(3)
+    d.check()
+
+
+# ---------------------------------------------------------------- replay ----
+
+def test_replay_is_deterministic_and_qas_helps():
+    from paper_2605_08581_amd import replay as R
+    from paper_2605_08581_amd import trace as T
+    tr = T.make_trace(400, 60.0, seed=5)
+    base = dict(num_pages=3072, prefill_rate=4e4)
+    a = R.replay(tr, R.ReplayConfig(policy="dart", **base), check_every=1)
+    b = R.replay(tr, R.ReplayConfig(policy="dart", **base))
+    assert a == b
+    lru = R.replay(tr, R.ReplayConfig(policy="lru", **base), check_every=5)
+    fifo = R.replay(tr, R.ReplayConfig(policy="lru", scheduler="fifo", **base))
+    assert a["requests"] == 400 and a["evicted_pages"] > 0
+    assert 0 < a["hit_rate"] < 1
+    # reordering plus grouping raises exact-prefix reuse (Sec. 3.2); demand-aware
+    # retention does not lose to plain recency (Sec. 5.4, cache-policy ablation)
+    assert lru["hit_rate"] > fifo["hit_rate"] * 1.5
+    assert a["hit_rate"] >= lru["hit_rate"]
+    assert a["evicted_by_class"][0] > 0 and a["evicted_by_class"][1] > 0
+    assert sum(lru["evicted_by_class"][1:]) == 0
