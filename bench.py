@@ -78,6 +78,12 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB (read + write), for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--uniform", default=None, metavar="P,S,B",
+                    help="diagnostic wave instead of --config: B requests of the 13B-class geometry, each "
+                         "with P cached and S new tokens on pages of its own (no ragged tiles)")
+    ap.add_argument("--alias-pages", type=int, default=0, metavar="N",
+                    help="diagnostic: fold the block table onto the first N pages so that K/V are served "
+                         "from cache instead of HBM (outputs are meaningless; timing and counters only)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -105,10 +111,17 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n}))
         return
 
-    if args.config == 3 and args.hit is not None:
+    if args.uniform:
+        P, S, nb = (int(x) for x in args.uniform.split(","))
+        b = W.make_custom_batch(f"uniform-P{P}-S{S}-B{nb}", W.Geometry(40, 40, 128), [P] * nb, [S] * nb, seed=1,
+                                permute_pages=False)
+    elif args.config == 3 and args.hit is not None:
         b = W.make_hit_rate_batch(args.hit)
     else:
         b = W.make_config(args.config)
+    if args.alias_pages:
+        b.block_table = (b.block_table % args.alias_pages).astype(np.int32)
+        b.name += f" (diagnostic: block table folded onto {args.alias_pages} pages)"
     acc = accounting(b)
     t = W.make_tensors(b, "cuda")
     pool_bytes = 2 * t["k_pool"].numel() * 2
@@ -189,7 +202,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{b.name} (benchmark configuration [{args.config}]): Hq={b.geom.num_q_heads} "
+        "config": {"workload": f"{b.name}{'' if args.uniform else f' (benchmark configuration [{args.config}])'}: "
+                               f"Hq={b.geom.num_q_heads} "
                                f"Hkv={b.geom.num_kv_heads} d={b.geom.head_dim} page=16 batch={b.batch}",
                    "prefix_tokens": int(b.prefix_len.sum()), "suffix_tokens": acc["suffix_tokens"],
                    "unique_pages": b.unique_pages_read(), "layer_pools_cycled": n_pools,

@@ -5,4 +5,4 @@ The compute lives in the HIP library under ``csrc/`` (C ABI declared in
 draws seeded synthetic inputs.  Importing the package loads nothing; the
 library is loaded on first use and its absence is an error, never a fallback.
 """
-__all__ = ["workload", "binding"]
+__all__ = ["workload", "binding", "sched", "trace", "replay", "queueing"]

@@ -164,6 +164,16 @@ constexpr float kRescaleThreshold = 8.0f;   // log2 units
 #define SG_MFMA 0x008
 #define SG_DSRD 0x100
 
+// f(integral_constant<int, B>) ... f(integral_constant<int, E-1>), expanded at
+// compile time: the body sees its index as a constant expression.
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 template <int D, int RB, int NW, int WPE, int NS>
 __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k_pool,
@@ -295,6 +305,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     }
   };
 
+  PageIds pg_v, pg_k;                             // page ids of tiles t+NS-1 and t+NS
+  // copy i (0 .. UPW-1) of this wave's share of a tile, as one instruction
+  auto copy_one = [&](const void *pool, int which, int slot, const PageIds &pg, auto it_) __attribute__((always_inline)) {
+    constexpr int i = decltype(it_)::value;
+    const int u = wave * UPW + i;
+    const unsigned char *blk = (const unsigned char *)pool + (int64_t)pg.p[i / UPP] * page_stride + head_off;
+    copy16_to_lds(block_resource(blk, kPage * D * 2), lane_src[i],
+                  lds_base + (uint32_t)((which * NS + slot) * TILE_BYTES + u * 1024));
+  };
   const int i16 = lane & 15;
   const int grp = (lane >> 4) & 1;
 
@@ -439,14 +458,21 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   // of chunks - one MFMA, one LDS fragment read three chunks ahead of its
   // use, and a slice of the exponentials - and the compiler's scheduler is
   // fenced between chunks, so the matrix pipe always has an MFMA queued while
-  // the vector ALU works through the softmax.
+  // the vector ALU works through the softmax.  When VSLOT/KSLOT name ring
+  // slots (>= 0), this wave's copies of the tiles that go into them are issued
+  // one at a time, spread evenly over the chunks, instead of in a burst before
+  // the step: a copy instruction that finds the load queue full then holds up
+  // one wave for a moment rather than every wave of the workgroup at once.
   constexpr int NQK = KB * KK;                    // S^T MFMAs per tile (per row block)
   constexpr int NPV = KS * DB;                    // O^T MFMAs per tile
   constexpr int NEL = KB * 16;                    // score elements per lane per row block
   constexpr int LA = 3;                           // fragment reads run this many chunks ahead
   constexpr int CSPAN = NQK + (KS - 1) * DB;      // chunks over which the exponentials spread
   auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], uint32_t k_next, uint32_t v_cur,
-                  int next_key0, auto mask_tag) __attribute__((always_inline)) {
+                  int next_key0, auto mask_tag, auto vslot_tag, auto kslot_tag) __attribute__((always_inline)) {
+    constexpr int VSLOT = decltype(vslot_tag)::value, KSLOT = decltype(kslot_tag)::value;
+    constexpr int NC = 2 * UPW;
+    constexpr int STRIDE = (NQK + NPV - DB) / (NC + 1) > 0 ? (NQK + NPV - DB) / (NC + 1) : 1;
     static_assert(RB == 1, "the overlapped step is written for one 32-row block per wave");
     const float mc = m_run[0] * scale_log2e;
     float sum = 0.f;
@@ -485,23 +511,34 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
         }
       }
     };
+    auto mid_copy = [&](int c) __attribute__((always_inline)) {   // V copies first, then K
+      if (VSLOT < 0) return;
+      static_for<0, NC>([&](auto kt) __attribute__((always_inline)) {
+        constexpr int k = decltype(kt)::value;
+        if (c == k * STRIDE + STRIDE - 1) {
+          if constexpr (k < UPW) copy_one(v_pool, 1, VSLOT, pg_v, std::integral_constant<int, k>{});
+          else copy_one(k_pool, 0, KSLOT, pg_k, std::integral_constant<int, k - UPW>{});
+        }
+      });
+    };
 #pragma unroll
     for (int i = 0; i < LA; ++i) fetch(i);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int c = 0; c < NQK + NPV; ++c) {
+    static_for<0, NQK + NPV>([&](auto ct_) __attribute__((always_inline)) {
+      constexpr int c = decltype(ct_)::value;
       fetch(c + LA);
-      if (c < NQK) {
+      if constexpr (c < NQK) {
         sn[c / KK][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], qf[0][c % KK],
                                                                 sn[c / KK][0], 0, 0, 0);
       } else {
-        const int j = c - NQK;
+        constexpr int j = c - NQK;
         oacc[j % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], pf[j / DB],
                                                                   oacc[j % DB][0], 0, 0, 0);
       }
       softmax_slice(c);
+      mid_copy(c);
       if (c < NQK + NPV - DB) __builtin_amdgcn_sched_barrier(0);
-    }
+    });
     l_run[0] += sum;
     if (decltype(mask_tag)::value) mask_tile(sn, next_key0);   // the next tile touches the diagonal
     raise_max(sn);
@@ -524,7 +561,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   };
   const bool wave_live = my_nt > 0;
   f32x16 s_a[KB][RB], s_b[KB][RB];
-  PageIds pg_v, pg_k;                             // page ids of tiles t+NS-1 and t+NS
   if (nt > 0) {
     PageIds pg = pages_of(0);
 #pragma unroll
@@ -569,10 +605,16 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     constexpr uint32_t k_next = (uint32_t)((j + 1) % NS) * TILE_BYTES;
     constexpr uint32_t v_cur = (uint32_t)(NS + j) * TILE_BYTES;
     arrive();
-    issue_copies((j + NS - 1) % NS, j, t);
     if (wave_live) {
-      if (j % 2 == 0) step(s_a, s_b, k_next, v_cur, 0, std::false_type{});
-      else step(s_b, s_a, k_next, v_cur, 0, std::false_type{});
+      // the step issues this iteration's copies itself, between its chunks
+      using VSlot = std::integral_constant<int, (j + NS - 1) % NS>;
+      using KSlot = std::integral_constant<int, j>;
+      if (j % 2 == 0) step(s_a, s_b, k_next, v_cur, 0, std::false_type{}, VSlot{}, KSlot{});
+      else step(s_b, s_a, k_next, v_cur, 0, std::false_type{}, VSlot{}, KSlot{});
+      pg_v = pg_k;
+      pg_k = pages_of(t + NS + 1);
+    } else {
+      issue_copies((j + NS - 1) % NS, j, t);      // a wave with no rows left only copies
     }
   };
   static_assert(NS == 2 || NS == 4, "the loop is unrolled for rings of 2 or 4 slots");
@@ -594,7 +636,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     arrive();
     issue_copies((t + NS - 1) % NS, t % NS, t);
     if (wave_live) {
-      step(s_a, s_b, k_slot(t + 1), v_slot(t), kv_begin + (t + 1) * BN, std::true_type{});
+      step(s_a, s_b, k_slot(t + 1), v_slot(t), kv_begin + (t + 1) * BN, std::true_type{},
+           std::integral_constant<int, -1>{}, std::integral_constant<int, -1>{});
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll

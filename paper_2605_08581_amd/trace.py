@@ -1,7 +1,7 @@
 """Seeded synthetic serving trace and content-addressed tensor values.
 
 Input generation only - none of the method's arithmetic lives here.  The trace
-follows the construction of Sec. 5.2 by its parameters (981 passages, a hot set
+follows the construction of Sec. 4.2 by its parameters (981 passages, a hot set
 of 20 drawn by a Zipf law with exponent 1.2, hot-request rate 0.7, k = 5
 retrieved 128-token segments, Poisson arrivals, 2048 requests); passages,
 system prefix and suffixes are random token ids, not text.

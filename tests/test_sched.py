@@ -461,7 +461,7 @@ def test_replay_is_deterministic_and_qas_helps():
     assert a["requests"] == 400 and a["evicted_pages"] > 0
     assert 0 < a["hit_rate"] < 1
     # reordering plus grouping raises exact-prefix reuse (Sec. 3.2); demand-aware
-    # retention does not lose to plain recency (Sec. 5.4, cache-policy ablation)
+    # retention does not lose to plain recency (Sec. 4.5, cache-policy ablation)
     assert lru["hit_rate"] > fifo["hit_rate"] * 1.5
     assert a["hit_rate"] >= lru["hit_rate"]
     assert a["evicted_by_class"][0] > 0 and a["evicted_by_class"][1] > 0
