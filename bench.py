@@ -196,6 +196,14 @@ def main():
         "reduce_ms": reduce_ms,
     })
 
+    # what this chip delivers on a bare MFMA loop and on a streaming read, beside the published peaks
+    scratch = torch.empty(2**30, dtype=torch.uint8, device="cuda").fill_(1)
+    peak_mfma, peak_read = B.prism_measure_peaks(scratch, repeats=3)
+    del scratch
+    measured = peak_mfma if roof["bound"] == "mfma" else peak_read
+    roof["measured_peak"] = {"mfma_tflops": peak_mfma, "hbm_read_gbs": peak_read,
+                             "frac_of_measured": roof["achieved"] / measured}
+
     result = {
         "metric": "prefix-cached prefill attention throughput", "value": acc["flops"] / elapsed * args.steps / 1e12,
         "unit": "TFLOP/s", "suffix_tokens_per_s": acc["suffix_tokens"] * args.steps / elapsed,

@@ -190,6 +190,19 @@ int prism_plan_profile_enable(prism_plan_t *plan, int enable);
 int prism_plan_profile_read(prism_plan_t *plan, double *append_ms, double *attention_ms,
                             double *reduce_ms, int32_t *launches);
 
+/*
+ * Measurement aid, not part of the method: what this chip delivers on a
+ * register-only loop of the same 32x32x16 bf16 MFMA the attention kernel uses
+ * (dense TFLOP/s over all compute units) and on a streaming read of
+ * scratch_dev (GB/s; give it at least 1 GiB so that caches cannot serve it),
+ * each the best of `repeats` timed launches after one warm-up.  bench.py prints
+ * these beside the published peaks.  scratch_dev is DEVICE memory owned by the
+ * caller, only read (>= 1 MiB).  Synchronous: waits for its own events on
+ * hip_stream.  PRISM_ERR_INVALID_ARG / PRISM_ERR_HIP on failure.
+ */
+int prism_measure_peaks(void *scratch_dev, size_t scratch_bytes, int32_t repeats, double *mfma_tflops,
+                        double *hbm_read_gbs, void *hip_stream);
+
 const char *prism_strerror(int code);
 const char *prism_last_hip_error(void);
 int prism_version(void);

@@ -23,7 +23,7 @@ EXPORTS = (
     "prism_version", "prism_strerror", "prism_last_hip_error", "prism_plan_create",
     "prism_plan_dry_run", "prism_plan_workspace_bytes", "prism_plan_get_info", "prism_plan_destroy", "prism_kv_append",
     "prism_prefix_attention", "prism_prefix_prefill", "prism_validate",
-    "prism_plan_profile_enable", "prism_plan_profile_read",
+    "prism_plan_profile_enable", "prism_plan_profile_read", "prism_measure_peaks",
 )
 
 
@@ -239,6 +239,22 @@ class Plan:
         if rc != PRISM_OK:
             raise PrismError(rc, "prism_plan_profile_read")
         return {"append_ms": a.value, "attention_ms": b.value, "reduce_ms": c.value, "launches": n.value}
+
+
+def prism_measure_peaks(scratch, repeats: int = 3):
+    """(MFMA TFLOP/s, streaming-read GB/s) measured on the current device;
+    scratch is a device tensor of at least 1 MiB (1 GiB or more for a
+    meaningful read figure)."""
+    lib = load()
+    m, h = ctypes.c_double(), ctypes.c_double()
+    lib.prism_measure_peaks.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                        ctypes.c_void_p]
+    rc = lib.prism_measure_peaks(_ptr(scratch), scratch.numel() * scratch.element_size(), repeats,
+                                 ctypes.byref(m), ctypes.byref(h), _stream())
+    if rc != PRISM_OK:
+        raise PrismError(rc, "prism_measure_peaks")
+    return m.value, h.value
 
 
 def shape_of(batch) -> Shape:

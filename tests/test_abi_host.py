@@ -165,3 +165,11 @@ def test_validate_flags_bad_tables(lib):
     bt[0, 3] = bt[0, 2]                        # one request maps two blocks to one page
     assert B.prism_validate(sh, b.prefix_len, b.suffix_len, bt) == B.ERR_TABLE
     assert B.prism_validate(sh, [32, 32, 5000], b.suffix_len, b.block_table) == B.ERR_INVALID_ARG
+
+
+def test_measure_peaks_rejects_bad_arguments(lib):
+    m, h = ctypes.c_double(), ctypes.c_double()
+    assert lib.prism_measure_peaks(None, 1 << 30, 1, ctypes.byref(m), ctypes.byref(h), None) == B.ERR_INVALID_ARG
+    assert lib.prism_measure_peaks(ctypes.c_void_p(4096), 16, 1, ctypes.byref(m), ctypes.byref(h), None) == B.ERR_INVALID_ARG
+    assert lib.prism_measure_peaks(ctypes.c_void_p(4096), 1 << 30, 0, ctypes.byref(m), ctypes.byref(h), None) == B.ERR_INVALID_ARG
+    assert lib.prism_measure_peaks(ctypes.c_void_p(4096), 1 << 30, 1, None, ctypes.byref(h), None) == B.ERR_INVALID_ARG

@@ -225,3 +225,13 @@ def test_single_token_suffix_decode_shape(oracle_lib, geom):
     b = W.make_custom_batch("decode", geom, [1000, 37, 4096, 16], [1, 1, 1, 1], seed=22)
     full_parity(oracle_lib, b)
     full_parity(oracle_lib, b, split_kv=4)
+
+
+def test_measured_peaks_are_plausible():
+    """The measurement aid reports machine ceilings below the published peaks
+    (2.5 PFLOP/s bf16 MFMA, 8 TB/s HBM) and well above zero."""
+    scratch = torch.ones(2**28, dtype=torch.uint8, device="cuda")
+    mfma, read = B.prism_measure_peaks(scratch, repeats=2)
+    assert 500.0 < mfma < 2500.0 * 1.02, mfma
+    assert 1000.0 < read < 8000.0 * 1.02, read
+    assert bool((scratch == 1).all()), "the scratch buffer is only read"
