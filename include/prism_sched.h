@@ -142,7 +142,14 @@ typedef struct prism_dart_options {
   int32_t policy;              /* PRISM_EVICT_*                                              */
   int32_t protect_budget;      /* f: anchors protected per round; 0 = 32; -1 = none          */
   int32_t first_page;          /* page ids handed out are first_page .. first_page+num_pages-1 */
-  int32_t reserved[3];
+  int32_t share_in_wave;       /* != 0: a request's pages are published at admission, so later
+                                  requests of the same wave reuse them although their KV is only
+                                  written by that wave.  Valid with prism_prefix_prefill, which
+                                  appends every request's suffix before any attention runs; such
+                                  tables break prism_validate's rule that no suffix write lands
+                                  in another request's prefix pages, by design.  0 = pages become
+                                  visible at prism_dart_commit (what the paper's engine does)  */
+  int32_t reserved[2];
 } prism_dart_options_t;
 
 /* An anchor: the span of `kind` (owner `segment`, ignored unless reusable)
@@ -158,6 +165,7 @@ typedef struct prism_dart_stats {
   int32_t num_pages, free_pages, tree_pages, private_pages;
   int32_t num_nodes, evictable_nodes, locked_nodes, protected_nodes;
   int64_t admitted_requests, admitted_tokens, hit_tokens;
+  int64_t in_wave_hit_tokens;  /* part of hit_tokens found on pages of the wave being formed */
   int64_t evicted_pages, evicted_nodes, evicted_by_class[3];
   int64_t heap_pops, heap_stale, heap_rebuilds;
 } prism_dart_stats_t;
@@ -192,7 +200,9 @@ int prism_dart_set_time(prism_dart_t *t, double now);
  * position up to n_tokens + reserve_tokens (decode budget), evicting if the
  * free list is short.  block_row[0..ceil((n_tokens+reserve_tokens)/page))
  * receives the page ids (row_capacity must cover them); *hit_tokens the hit
- * length.  The anchors are kept for prism_dart_commit.
+ * length.  The anchors are kept for prism_dart_commit.  With share_in_wave the
+ * request's whole pages are published here (and stay marked as pending until
+ * its prism_dart_commit).
  */
 int prism_dart_admit(prism_dart_t *t, int64_t request, const int32_t *tokens, int32_t n_tokens,
                      const prism_dart_anchor_t *anchors, int32_t n_anchors, int32_t reserve_tokens,

@@ -380,6 +380,7 @@ struct Node {
   uint32_t hits = 0, gen = 0;
   double last = 0;
   bool attached = false, is_protected = false;
+  bool pending = false;  // published at admission: its KV is written by the wave now forming
 };
 
 struct DReq {
@@ -388,7 +389,7 @@ struct DReq {
   std::vector<int32_t> row;
   std::vector<uint8_t> own;  // row[j] belongs to this request alone
   int32_t lock = 0;          // deepest locked node (0 = root: nothing locked)
-  bool committed = false;
+  bool committed = false, published = false;
 };
 
 struct Prio {
@@ -493,7 +494,7 @@ struct prism_dart {
     un.ref = cn.ref; un.kind = cn.kind; un.segment = cn.segment;
     un.end_offset = cn.end_offset - (int32_t)cn.pages.size() * ps;
     un.snap_g = cn.snap_g; un.snap_a = cn.snap_a; un.snap_n = cn.snap_n;
-    un.hits = cn.hits; un.last = cn.last; un.is_protected = false;
+    un.hits = cn.hits; un.last = cn.last; un.is_protected = false; un.pending = cn.pending;
     link(parent, u);
     link(u, c);
     return u;
@@ -501,8 +502,9 @@ struct prism_dart {
 
   // Walk down as far as whole pages of tok match, at most max_pages; cuts an edge
   // that matches only in part.  Returns the deepest node; *matched = pages.
-  int32_t match(const int32_t *tok, int32_t max_pages, bool touch, std::vector<int32_t> *row, int32_t *matched) {
-    int32_t cur = 0, pos = 0;
+  int32_t match(const int32_t *tok, int32_t max_pages, bool touch, std::vector<int32_t> *row, int32_t *matched,
+                int32_t *matched_pending = nullptr) {
+    int32_t cur = 0, pos = 0, pend = 0;
     while (pos < max_pages) {
       int32_t c = find_child(cur, tok + (size_t)pos * ps);
       if (c < 0) break;
@@ -513,12 +515,14 @@ struct prism_dart {
                                     sizeof(int32_t) * ps) == 0) ++k;
       if (k < len) c = split(c, k);
       if (touch) { nodes[c].last = now; nodes[c].hits++; }
+      if (nodes[c].pending) pend += k;
       if (row) for (int32_t j = 0; j < k; ++j) (*row)[pos + j] = nodes[c].pages[j];
       cur = c;
       pos += k;
       if (k < len) break;
     }
     *matched = pos;
+    if (matched_pending) *matched_pending = pend;
     return cur;
   }
 
@@ -605,6 +609,76 @@ struct prism_dart {
     return n_evicted;
   }
 
+  // Put the whole pages of request r into the tree, cut at its anchors, and move
+  // its lock to the deepest node (the body of commit; with in-wave sharing it
+  // runs at admission and marks the nodes it creates as pending).
+  void publish(DReq &r, bool mark_pending) {
+    const int32_t n_full = (int32_t)r.tok.size() / ps;
+    // Span limits in pages: a page belongs to the span that holds its last token,
+    // so the page that straddles a boundary goes with the later span.
+    struct Span { int32_t hi, kind, segment, end_offset; };
+    std::vector<Span> spans;
+    for (const prism_dart_anchor_t &a : r.anchors) {
+      int32_t hi = std::min(a.end_offset / ps, n_full);
+      if (hi > (spans.empty() ? 0 : spans.back().hi)) spans.push_back({hi, a.kind, a.segment, a.end_offset});
+    }
+    if (spans.empty() || spans.back().hi < n_full) spans.push_back({n_full, PRISM_SPAN_NONE, -1, n_full * ps});
+    int32_t cur = 0, pos = 0;
+    size_t si = 0;
+    while (pos < n_full) {
+      while (spans[si].hi <= pos) ++si;
+      const Span &sp = spans[si];
+      const int32_t *tp = r.tok.data() + (size_t)pos * ps;
+      int32_t c = find_child(cur, tp);
+      int32_t k;
+      if (c < 0) {
+        c = new_node();
+        Node &n = nodes[c];
+        n.pending = mark_pending;
+        k = sp.hi - pos;
+        n.tok.assign(tp, tp + (size_t)k * ps);
+        n.pages.assign(r.row.begin() + pos, r.row.begin() + pos + k);
+        for (int32_t j = pos; j < pos + k; ++j) r.own[j] = 0;
+        st.private_pages -= k;
+        st.tree_pages += k;
+        link(cur, c);
+      } else {
+        const int32_t len = (int32_t)nodes[c].pages.size();
+        const int32_t lim = std::min(len, sp.hi - pos);
+        k = 1;
+        while (k < lim && std::memcmp(nodes[c].tok.data() + (size_t)k * ps, tp + (size_t)k * ps,
+                                      sizeof(int32_t) * ps) == 0) ++k;
+        if (k < len) c = split(c, k);
+        Node &n = nodes[c];
+        for (int32_t j = 0; j < k; ++j) {
+          if (r.own[pos + j]) {  // someone else published the same content first
+            free_pages.push_back(r.row[pos + j]);
+            r.own[pos + j] = 0;
+            st.private_pages--;
+          }
+          r.row[pos + j] = n.pages[j];
+        }
+      }
+      Node &n = nodes[c];
+      n.kind = sp.kind;
+      n.segment = sp.kind == PRISM_SPAN_REUSABLE ? sp.segment : -1;
+      n.end_offset = (pos + k) * ps;
+      if (n.kind == PRISM_SPAN_REUSABLE) {
+        auto pit = prio.find(n.segment);
+        if (pit != prio.end()) { n.snap_g = pit->second.g; n.snap_a = pit->second.a; n.snap_n = pit->second.n; }
+      }
+      n.last = now;
+      cur = c;
+      pos += k;
+    }
+    if (cur != r.lock) {
+      lock(cur);
+      unlock(r.lock);
+      r.lock = cur;
+    }
+    r.published = true;
+  }
+
   bool alloc(int32_t n, std::vector<int32_t> &out) {
     if ((int32_t)free_pages.size() < n) evict((int64_t)(n - (int32_t)free_pages.size()) * ps, nullptr);
     if ((int32_t)free_pages.size() < n) return false;
@@ -677,8 +751,8 @@ extern "C" int prism_dart_admit(prism_dart_t *t, int64_t request, const int32_t 
   r.anchors.assign(anchors, anchors + n_anchors);
   r.row.assign(total_pages, -1);
   r.own.assign(total_pages, 0);
-  int32_t matched = 0;
-  r.lock = t->match(tokens, (n_tokens - 1) / ps, true, &r.row, &matched);
+  int32_t matched = 0, matched_pending = 0;
+  r.lock = t->match(tokens, (n_tokens - 1) / ps, true, &r.row, &matched, &matched_pending);
   t->lock(r.lock);
   std::vector<int32_t> fresh;
   if (!t->alloc(total_pages - matched, fresh)) {
@@ -686,9 +760,11 @@ extern "C" int prism_dart_admit(prism_dart_t *t, int64_t request, const int32_t 
     return PRISM_ERR_NO_MEMORY;
   }
   for (int32_t j = matched; j < total_pages; ++j) { r.row[j] = fresh[j - matched]; r.own[j] = 1; }
+  t->st.private_pages += total_pages - matched;
+  if (t->opt.share_in_wave) t->publish(r, true);
   std::memcpy(block_row, r.row.data(), sizeof(int32_t) * total_pages);
   *hit_tokens = matched * ps;
-  t->st.private_pages += total_pages - matched;
+  t->st.in_wave_hit_tokens += (int64_t)matched_pending * ps;
   t->st.admitted_requests++;
   t->st.admitted_tokens += n_tokens;
   t->st.hit_tokens += (int64_t)matched * ps;
@@ -702,68 +778,12 @@ extern "C" int prism_dart_commit(prism_dart_t *t, int64_t request, int32_t *bloc
   if (it == t->reqs.end() || it->second.committed) return PRISM_ERR_INVALID_ARG;
   DReq &r = it->second;
   if (block_row && row_capacity < (int32_t)r.row.size()) return PRISM_ERR_INVALID_ARG;
-  const int32_t ps = t->ps;
-  const int32_t n_full = (int32_t)r.tok.size() / ps;
-  // Span limits in pages: a page belongs to the span that holds its last token,
-  // so the page that straddles a boundary goes with the later span.
-  struct Span { int32_t hi, kind, segment, end_offset; };
-  std::vector<Span> spans;
-  for (const prism_dart_anchor_t &a : r.anchors) {
-    int32_t hi = std::min(a.end_offset / ps, n_full);
-    if (hi > (spans.empty() ? 0 : spans.back().hi)) spans.push_back({hi, a.kind, a.segment, a.end_offset});
-  }
-  if (spans.empty() || spans.back().hi < n_full) spans.push_back({n_full, PRISM_SPAN_NONE, -1, n_full * ps});
-  int32_t cur = 0, pos = 0;
-  size_t si = 0;
-  while (pos < n_full) {
-    while (spans[si].hi <= pos) ++si;
-    const Span &sp = spans[si];
-    const int32_t *tp = r.tok.data() + (size_t)pos * ps;
-    int32_t c = t->find_child(cur, tp);
-    int32_t k;
-    if (c < 0) {
-      c = t->new_node();
-      Node &n = t->nodes[c];
-      k = sp.hi - pos;
-      n.tok.assign(tp, tp + (size_t)k * ps);
-      n.pages.assign(r.row.begin() + pos, r.row.begin() + pos + k);
-      for (int32_t j = pos; j < pos + k; ++j) r.own[j] = 0;
-      t->st.private_pages -= k;
-      t->st.tree_pages += k;
-      t->link(cur, c);
-    } else {
-      const int32_t len = (int32_t)t->nodes[c].pages.size();
-      const int32_t lim = std::min(len, sp.hi - pos);
-      k = 1;
-      while (k < lim && std::memcmp(t->nodes[c].tok.data() + (size_t)k * ps, tp + (size_t)k * ps,
-                                    sizeof(int32_t) * ps) == 0) ++k;
-      if (k < len) c = t->split(c, k);
-      Node &n = t->nodes[c];
-      for (int32_t j = 0; j < k; ++j) {
-        if (r.own[pos + j]) {  // someone else published the same content first
-          t->free_pages.push_back(r.row[pos + j]);
-          r.own[pos + j] = 0;
-          t->st.private_pages--;
-        }
-        r.row[pos + j] = n.pages[j];
-      }
-    }
-    Node &n = t->nodes[c];
-    n.kind = sp.kind;
-    n.segment = sp.kind == PRISM_SPAN_REUSABLE ? sp.segment : -1;
-    n.end_offset = (pos + k) * ps;
-    if (n.kind == PRISM_SPAN_REUSABLE) {
-      auto pit = t->prio.find(n.segment);
-      if (pit != t->prio.end()) { n.snap_g = pit->second.g; n.snap_a = pit->second.a; n.snap_n = pit->second.n; }
-    }
-    n.last = t->now;
-    cur = c;
-    pos += k;
-  }
-  if (cur != r.lock) {
-    t->lock(cur);
-    t->unlock(r.lock);
-    r.lock = cur;
+  if (r.published) {
+    // published at admission (in-wave sharing): the wave has run, so the KV of
+    // the nodes this request created now exists
+    for (int32_t u = r.lock; u != 0; u = t->nodes[u].parent) t->nodes[u].pending = false;
+  } else {
+    t->publish(r, false);
   }
   r.committed = true;
   if (block_row) std::memcpy(block_row, r.row.data(), sizeof(int32_t) * r.row.size());

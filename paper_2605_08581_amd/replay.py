@@ -42,6 +42,7 @@ class ReplayConfig:
     prefill_rate: float = 4.0e4    # tokens/s of uncached prefill work
     t_fixed: float = 0.004         # per-wave overhead, seconds
     t_token: float = 0.008         # per decoded token, seconds
+    share_in_wave: bool = False    # publish pages at admission: requests of one wave reuse each other's
 
 
 @dataclass
@@ -62,7 +63,8 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
     returns its GPU milliseconds.  Returns the summary statistics."""
     qas = S.Qas(cfg.dispatch_budget, cold_quota=cfg.cold_quota,
                 mode=S.QAS_MODE_FIFO if cfg.scheduler == "fifo" else S.QAS_MODE_QAS)
-    dart = S.Dart(cfg.num_pages, policy=S.POLICIES[cfg.policy], protect_budget=cfg.protect_budget)
+    dart = S.Dart(cfg.num_pages, policy=S.POLICIES[cfg.policy], protect_budget=cfg.protect_budget,
+                  share_in_wave=cfg.share_in_wave)
     reqs = trace.requests
     by_id = {r.id: r for r in reqs}
     seg_len = trace.segment_tokens
@@ -144,6 +146,7 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
     pct = lambda p: float(tt[min(len(tt) - 1, int(math.ceil(p / 100.0 * len(tt))) - 1)])
     out = dict(config=asdict(cfg), requests=len(reqs), waves=waves, mean_wave_size=float(np.mean(wave_sizes)),
                hit_rate=total_hit / max(1, total_tokens), prompt_tokens=total_tokens, hit_tokens=total_hit,
+               in_wave_hit_tokens=int(st.in_wave_hit_tokens),
                mean_uncached_per_wave=float(np.mean(uncached_per_wave)),
                ttft_mean=float(tt.mean()), ttft_p50=pct(50), ttft_p90=pct(90), ttft_p99=pct(99),
                makespan=busy_until, memory_stalls=stalls, evicted_pages=int(st.evicted_pages), evicted_nodes=int(st.evicted_nodes),
@@ -215,13 +218,15 @@ def main(argv=None) -> int:
     ap.add_argument("--cold", type=int, default=ReplayConfig.cold_quota)
     ap.add_argument("--protect", type=int, default=0)
     ap.add_argument("--seed", type=int, default=20260508)
+    ap.add_argument("--share-in-wave", action="store_true",
+                    help="requests of one wave reuse each other's pages (the prefill call appends before it attends)")
     ap.add_argument("--gpu", action="store_true", help="prefill every wave on cuda:0 and report GPU time")
     ap.add_argument("--heads", default="40,40,128", help="Hq,Hkv,d of the device run")
     args = ap.parse_args(argv)
     trace = T.make_trace(args.requests, args.qps, args.seed)
     for pol in args.policy.split(","):
         cfg = ReplayConfig(policy=pol, scheduler=args.scheduler, dispatch_budget=args.budget, cold_quota=args.cold,
-                           num_pages=args.pages, protect_budget=args.protect)
+                           num_pages=args.pages, protect_budget=args.protect, share_in_wave=args.share_in_wave)
         runner = None
         if args.gpu:
             hq, hkv, d = (int(x) for x in args.heads.split(","))

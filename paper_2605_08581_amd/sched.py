@@ -48,7 +48,7 @@ class QasPriority(ctypes.Structure):
 
 class DartOptions(ctypes.Structure):
     _fields_ = [("num_pages", i32), ("page_size", i32), ("policy", i32), ("protect_budget", i32),
-                ("first_page", i32), ("reserved", i32 * 3)]
+                ("first_page", i32), ("share_in_wave", i32), ("reserved", i32 * 2)]
 
 
 class DartAnchor(ctypes.Structure):
@@ -59,6 +59,7 @@ class DartStats(ctypes.Structure):
     _fields_ = [("num_pages", i32), ("free_pages", i32), ("tree_pages", i32), ("private_pages", i32),
                 ("num_nodes", i32), ("evictable_nodes", i32), ("locked_nodes", i32), ("protected_nodes", i32),
                 ("admitted_requests", i64), ("admitted_tokens", i64), ("hit_tokens", i64),
+                ("in_wave_hit_tokens", i64),
                 ("evicted_pages", i64), ("evicted_nodes", i64), ("evicted_by_class", i64 * 3),
                 ("heap_pops", i64), ("heap_stale", i64), ("heap_rebuilds", i64)]
 
@@ -188,10 +189,10 @@ class Dart:
     """The radix tree over cached pages with Eq. 13 / Alg. 2 eviction."""
 
     def __init__(self, num_pages: int, policy: int = EVICT_DART, protect_budget: int = 0, page_size: int = 16,
-                 first_page: int = 0):
+                 first_page: int = 0, share_in_wave: bool = False):
         lib = _lib()
         o = DartOptions(num_pages=num_pages, page_size=page_size, policy=policy, protect_budget=protect_budget,
-                        first_page=first_page)
+                        first_page=first_page, share_in_wave=int(share_in_wave))
         self.page_size = page_size
         self._h = ctypes.c_void_p()
         _check(lib.prism_dart_create(ctypes.byref(o), ctypes.byref(self._h)), "prism_dart_create")

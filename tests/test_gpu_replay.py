@@ -53,10 +53,10 @@ def _from_scratch(oracle_lib, rec):
                                 1.0 / math.sqrt(D))
 
 
-@pytest.mark.parametrize("policy", ["dart", "lru"])
-def test_replayed_waves_equal_from_scratch_prefill(oracle_lib, policy):
+@pytest.mark.parametrize("policy,share", [("dart", False), ("lru", False), ("dart", True)])
+def test_replayed_waves_equal_from_scratch_prefill(oracle_lib, policy, share):
     tr = T.make_trace(120, 150.0, seed=11, num_passages=60, hot_set=8, segment_tokens=64, suffix_range=(9, 50))
-    cfg = R.ReplayConfig(policy=policy, dispatch_budget=8, num_pages=900, prefill_rate=4e4)
+    cfg = R.ReplayConfig(policy=policy, dispatch_budget=8, num_pages=900, prefill_rate=4e4, share_in_wave=share)
     runner = R.DeviceRunner(cfg.num_pages, HQ, HKV, D, keep_outputs=True)
     state = dict(waves=0, checked=0, hit=0, reused_after_eviction=False)
 
@@ -88,6 +88,8 @@ def test_replayed_waves_equal_from_scratch_prefill(oracle_lib, policy):
     assert res["evicted_pages"] > 0, "the pool never filled: no reuse-after-eviction was exercised"
     assert res["hit_tokens"] == state["hit"] and res["hit_tokens"] > 0
     assert res["gpu_ms_per_wave"] > 0
+    # in-wave reuse reads pages that the same call's append kernel has just written
+    assert (res["in_wave_hit_tokens"] > 0) == share
     # the device run changes nothing in the control decisions
     again = R.replay(tr, cfg)
     for key in ("waves", "hit_tokens", "evicted_pages", "evicted_by_class", "ttft_p99"):

@@ -267,6 +267,35 @@ def test_dart_same_wave_duplicates_are_merged_at_commit():
     assert d.peek(toks) == ((len(toks) - 1) // PAGE) * PAGE
 
 
+def test_dart_in_wave_sharing_publishes_at_admission():
+    """With share_in_wave the second request of a wave reuses the first one's
+    pages although their KV is only written by that wave (Eq. 3 applied to the
+    wave being formed); without it both miss."""
+    rng = random.Random(4)
+    lib = _seg_lib(rng, 2, lens=(64,))
+    toks_a, anch_a = _prompt(rng, [0, 1], lib, [], 20)
+    toks_b, anch_b = _prompt(rng, [0, 1], lib, [], 37)          # same segments, other suffix
+    d = S.Dart(num_pages=200, share_in_wave=True)
+    ha, ra = d.admit(1, toks_a, anch_a)
+    hb, rb = d.admit(2, toks_b, anch_b)
+    assert ha == 0 and hb == 128
+    assert (rb[:8] == ra[:8]).all() and not set(rb[8:].tolist()) & set(ra.tolist())
+    st = d.stats()
+    assert st.hit_tokens == 128 and st.in_wave_hit_tokens == 128
+    d.check()
+    # pending nodes are locked by their creator: nothing can be evicted from under the wave
+    assert d.evict(10 ** 6) == (0, 0)
+    ra2, rb2 = d.commit(1, ra.copy()), d.commit(2, rb.copy())
+    assert (ra2 == ra).all() and (rb2 == rb).all()                # commit changes nothing any more
+    hc, _ = d.admit(3, toks_a, anch_a)                            # next wave: an ordinary hit
+    assert hc == ((len(toks_a) - 1) // PAGE) * PAGE
+    assert d.stats().in_wave_hit_tokens == 128
+    for rid in (1, 2, 3):
+        d.release(rid)
+    d.check()
+    assert ref.hit_length(toks_b, [toks_a]) == 128
+
+
 def test_dart_splits_existing_edge_at_anchor():
     rng = random.Random(2)
     lib = _seg_lib(rng, 3, lens=(48,))
@@ -466,3 +495,6 @@ def test_replay_is_deterministic_and_qas_helps():
     assert a["hit_rate"] >= lru["hit_rate"]
     assert a["evicted_by_class"][0] > 0 and a["evicted_by_class"][1] > 0
     assert sum(lru["evicted_by_class"][1:]) == 0
+    shared = R.replay(tr, R.ReplayConfig(policy="dart", share_in_wave=True, **base), check_every=1)
+    assert shared["in_wave_hit_tokens"] > 0 and a["in_wave_hit_tokens"] == 0
+    assert shared["hit_rate"] > a["hit_rate"]
