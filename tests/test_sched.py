@@ -246,6 +246,37 @@ def test_dart_hits_equal_brute_force_without_pressure(seed):
     assert st.free_pages + st.tree_pages + st.private_pages == st.num_pages
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_dart_in_wave_hits_equal_brute_force(seed):
+    """share_in_wave: a request sees everything admitted before it, committed or not."""
+    rng = random.Random(50 + seed)
+    lib = _seg_lib(rng, 5)
+    sys_t = [rng.randrange(32000) for _ in range(rng.choice([0, 16, 21]))]
+    d = S.Dart(num_pages=20000, share_in_wave=True)
+    admitted, waves, rid = [], [], 0
+    for wave in range(12):
+        members = []
+        for _ in range(rng.randint(1, 5)):
+            d.set_time(float(rid))
+            toks, anchors = _prompt(rng, [rng.randrange(5) for _ in range(rng.randint(0, 3))], lib, sys_t, rng.randint(1, 30))
+            hit, row = d.admit(rid, toks, anchors, reserve_tokens=rng.choice([0, 32]))
+            assert hit == ref.hit_length(toks, admitted)
+            admitted.append(toks)
+            members.append((rid, row))
+            rid += 1
+            d.check()
+        for r, row in members:
+            before = row.copy()
+            d.commit(r, row)
+            assert (row == before).all()
+        waves.append(members)
+        if len(waves) > 2:
+            for r, _ in waves.pop(0):
+                d.release(r)
+        d.check()
+    assert d.stats().in_wave_hit_tokens > 0
+
+
 def test_dart_same_wave_duplicates_are_merged_at_commit():
     rng = random.Random(1)
     lib = _seg_lib(rng, 2, lens=(64,))
