@@ -154,15 +154,6 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
 
-// sched_group_barrier masks
-#define SG_VALU 0x002
-#ifndef EXP_NO_SGB
-#define SGB(a, b) __builtin_amdgcn_sched_group_barrier(a, b, 0)
-#else
-#define SGB(a, b)
-#endif
-#define SG_MFMA 0x008
-#define SG_DSRD 0x100
 
 // f(integral_constant<int, B>) ... f(integral_constant<int, E-1>), expanded at
 // compile time: the body sees its index as a constant expression.

@@ -235,3 +235,43 @@ def test_measured_peaks_are_plausible():
     assert 500.0 < mfma < 2500.0 * 1.02, mfma
     assert 1000.0 < read < 8000.0 * 1.02, read
     assert bool((scratch == 1).all()), "the scratch buffer is only read"
+
+
+def test_pages_beyond_the_4_gib_offset(oracle_lib):
+    """Byte offsets into the pools exceed 32 bits: a 4.6 GB pool whose used
+    pages sit at its far end (and its very start).  The oracle sees the same
+    pages compacted into a small pool."""
+    geom = W.Geometry(8, 8, 128)
+    small = W.make_custom_batch("far-pages", geom, [160, 47], [40, 70], seed=3)
+    used = sorted(set(int(p) for r in range(small.batch)
+                      for p in small.block_table[r, :(small.prefix_len[r] + small.suffix_len[r] + 15) // 16]))
+    num_pages = 140_000                                      # x 8 heads x 16 x 128 x 2 B = 4.59 GB per pool
+    far = {p: (num_pages - 1 - 977 * i if i % 2 == 0 else 3 * i) for i, p in enumerate(used)}
+    assert max(far.values()) * 8 * 16 * 128 * 2 > 2**32 and len(set(far.values())) == len(far)
+    t = W.make_tensors(small, "cuda")
+    big = {k: torch.zeros(num_pages, 8, 16, 128, dtype=torch.bfloat16, device="cuda") for k in ("k_pool", "v_pool")}
+    for p, q_ in far.items():
+        big["k_pool"][q_] = t["k_pool"][p]
+        big["v_pool"][q_] = t["v_pool"][p]
+    table = small.block_table.copy()
+    for p, q_ in far.items():
+        table[small.block_table == p] = q_
+    shape = B.make_shape(8, 8, 128, num_pages, small.batch, small.max_blocks, small.softmax_scale)
+    plan = B.Plan(shape, small.prefix_len, small.suffix_len, block_table=table)
+    bt = torch.from_numpy(table).cuda()
+    out = torch.full_like(t["q"], float("nan"))
+    plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], big["k_pool"], big["v_pool"], bt, out, None)
+    torch.cuda.synchronize()
+    plan.close()
+    host = {k: W.bf16_bits(v) for k, v in t.items()}
+    kp, vp = oracle_lib.kv_append(host["k_suffix"], host["v_suffix"], host["k_pool"], host["v_pool"],
+                                  small.block_table, small.prefix_len, small.suffix_len)
+    for p, q_ in far.items():                                # the appended pages, bit for bit, where they belong
+        assert np.array_equal(W.bf16_bits(big["k_pool"][q_]), kp[p])
+        assert np.array_equal(W.bf16_bits(big["v_pool"][q_]), vp[p])
+    untouched = torch.ones(num_pages, dtype=torch.bool, device="cuda")
+    untouched[torch.tensor(sorted(far.values()), device="cuda")] = False
+    assert not bool(big["k_pool"][untouched].any()) and not bool(big["v_pool"][untouched].any())
+    ref = oracle_lib.attention(host["q"], kp, vp, small.block_table, small.prefix_len, small.suffix_len,
+                               small.softmax_scale)
+    check_close(widen(W.bf16_bits(out)), ref, "far pages")
