@@ -19,6 +19,7 @@ import argparse
 import heapq
 import json
 import math
+import time
 from dataclasses import dataclass, asdict
 from typing import Callable, List, Optional
 
@@ -72,6 +73,7 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
     done_heap: list = []
     ttft, wave_sizes, gpu_ms, uncached_per_wave = [], [], [], []
     total_tokens = total_hit = waves = stalls = 0
+    t_sched = t_tree = 0.0                         # host seconds spent inside the scheduler / the radix tree
     while nxt < len(reqs) or qas.pending > 0:
         t = max(t + cfg.window, busy_until)
         if qas.pending == 0 and nxt < len(reqs) and reqs[nxt].arrival > t:
@@ -85,10 +87,14 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
             _, rid = heapq.heappop(done_heap)
             qas.complete(rid)
             dart.release(rid)
+        c0 = time.perf_counter()
         hints, segs, pri = qas.round()
+        t_sched += time.perf_counter() - c0
         if not hints:
             continue
+        c0 = time.perf_counter()
         dart.set_round(t, pri)
+        t_tree += time.perf_counter() - c0
         rec = WaveRecord(t, [], [], [], [], [], 0.0)
         for h in hints:
             r = by_id[h.request]
@@ -99,7 +105,9 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
             anchors.append((len(tokens), S.SPAN_PRIVATE, -1))
             while True:
                 try:
+                    c0 = time.perf_counter()
                     hit, row = dart.admit(r.id, tokens, anchors, reserve_tokens=cfg.decode_tokens)
+                    t_tree += time.perf_counter() - c0
                     break
                 except B.PrismError as e:
                     # pool exhausted by locked pages: the backend stalls until the
@@ -126,7 +134,9 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
         busy_until = t + rec.service
         dart.set_time(busy_until)
         for rid, row in zip(rec.requests, rec.rows):
+            c0 = time.perf_counter()
             dart.commit(rid, row)
+            t_tree += time.perf_counter() - c0
             ttft.append(busy_until - by_id[rid].arrival)
             heapq.heappush(done_heap, (busy_until + cfg.decode_tokens * cfg.t_token, rid))
         waves += 1
@@ -151,7 +161,8 @@ def replay(trace: T.Trace, cfg: ReplayConfig, on_wave: Optional[Callable[[WaveRe
                ttft_mean=float(tt.mean()), ttft_p50=pct(50), ttft_p90=pct(90), ttft_p99=pct(99),
                makespan=busy_until, memory_stalls=stalls, evicted_pages=int(st.evicted_pages), evicted_nodes=int(st.evicted_nodes),
                evicted_by_class=[int(x) for x in st.evicted_by_class], heap_pops=int(st.heap_pops),
-               heap_stale=int(st.heap_stale), heap_rebuilds=int(st.heap_rebuilds), tree_nodes=int(st.num_nodes))
+               heap_stale=int(st.heap_stale), heap_rebuilds=int(st.heap_rebuilds), tree_nodes=int(st.num_nodes),
+               scheduler_ms_per_wave=1e3 * t_sched / max(1, waves), tree_ms_per_wave=1e3 * t_tree / max(1, waves))
     if gpu_ms:
         out["gpu_ms_per_wave"] = float(np.mean(gpu_ms))
         out["gpu_ms_total"] = float(np.sum(gpu_ms))

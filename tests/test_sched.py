@@ -515,7 +515,9 @@ def test_replay_is_deterministic_and_qas_helps():
     base = dict(num_pages=3072, prefill_rate=4e4)
     a = R.replay(tr, R.ReplayConfig(policy="dart", **base), check_every=1)
     b = R.replay(tr, R.ReplayConfig(policy="dart", **base))
-    assert a == b
+    timing = ("scheduler_ms_per_wave", "tree_ms_per_wave")
+    assert {k: v for k, v in a.items() if k not in timing} == {k: v for k, v in b.items() if k not in timing}
+    assert all(a[k] > 0 for k in timing)
     lru = R.replay(tr, R.ReplayConfig(policy="lru", **base), check_every=5)
     fifo = R.replay(tr, R.ReplayConfig(policy="lru", scheduler="fifo", **base))
     assert a["requests"] == 400 and a["evicted_pages"] > 0
