@@ -451,9 +451,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   // fenced between chunks, so the matrix pipe always has an MFMA queued while
   // the vector ALU works through the softmax.  When VSLOT/KSLOT name ring
   // slots (>= 0), this wave's copies of the tiles that go into them are issued
-  // one at a time, spread evenly over the chunks, instead of in a burst before
-  // the step: a copy instruction that finds the load queue full then holds up
-  // one wave for a moment rather than every wave of the workgroup at once.
+  // one at a time between the first chunks (every other one), instead of in a
+  // burst before the step: a copy instruction that finds the load queue full
+  // then holds up one wave for a moment rather than every wave of the
+  // workgroup at once, and the data still has most of an iteration to arrive.
   constexpr int NQK = KB * KK;                    // S^T MFMAs per tile (per row block)
   constexpr int NPV = KS * DB;                    // O^T MFMAs per tile
   constexpr int NEL = KB * 16;                    // score elements per lane per row block
@@ -463,7 +464,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
                   int next_key0, auto mask_tag, auto vslot_tag, auto kslot_tag) __attribute__((always_inline)) {
     constexpr int VSLOT = decltype(vslot_tag)::value, KSLOT = decltype(kslot_tag)::value;
     constexpr int NC = 2 * UPW;
-    constexpr int STRIDE = (NQK + NPV - DB) / (NC + 1) > 0 ? (NQK + NPV - DB) / (NC + 1) : 1;
+    constexpr int STRIDE = 2 * NC <= NQK + NPV ? 2 : 1;   // every other chunk from the start of the step
     static_assert(RB == 1, "the overlapped step is written for one 32-row block per wave");
     const float mc = m_run[0] * scale_log2e;
     float sum_even = 0.f, sum_odd = 0.f;          // two chains: no add waits on the one before it
