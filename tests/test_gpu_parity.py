@@ -275,3 +275,33 @@ def test_pages_beyond_the_4_gib_offset(oracle_lib):
     ref = oracle_lib.attention(host["q"], kp, vp, small.block_table, small.prefix_len, small.suffix_len,
                                small.softmax_scale)
     check_close(widen(W.bf16_bits(out)), ref, "far pages")
+
+
+def test_two_plans_on_two_streams(oracle_lib):
+    """Calls on distinct plans are independent: two waves enqueued on two
+    streams of default priority, overlapping in time, both match the oracle."""
+    waves = [W.make_custom_batch("stream-a", W.Geometry(8, 2, 128), [1000, 37, 512], [90, 200, 33], seed=21),
+             W.make_custom_batch("stream-b", W.Geometry(4, 4, 64), [300, 2000], [129, 64], seed=22)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    state = []
+    for b, st in zip(waves, streams):
+        t = W.make_tensors(b, "cuda")
+        host = {k: W.bf16_bits(v) for k, v in t.items()}
+        plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, block_table=b.block_table, split_kv=2)
+        bt = torch.from_numpy(b.block_table).cuda()
+        out = torch.full_like(t["q"], float("nan"))
+        ws = torch.empty(max(plan.prism_plan_workspace_bytes(), 256), dtype=torch.uint8, device="cuda")
+        state.append((b, t, host, plan, bt, out, ws, st))
+    torch.cuda.synchronize()
+    for rep in range(3):                                     # several launches in flight on each stream
+        for b, t, host, plan, bt, out, ws, st in state:
+            with torch.cuda.stream(st):
+                plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], t["k_pool"], t["v_pool"], bt, out, ws)
+    torch.cuda.synchronize()
+    for b, t, host, plan, bt, out, ws, st in state:
+        plan.close()
+        kp, vp = oracle_lib.kv_append(host["k_suffix"], host["v_suffix"], host["k_pool"], host["v_pool"],
+                                      b.block_table, b.prefix_len, b.suffix_len)
+        assert np.array_equal(W.bf16_bits(t["k_pool"]), kp) and np.array_equal(W.bf16_bits(t["v_pool"]), vp)
+        ref = oracle_lib.attention(host["q"], kp, vp, b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale)
+        check_close(widen(W.bf16_bits(out)), ref, b.name)
