@@ -305,3 +305,39 @@ def test_two_plans_on_two_streams(oracle_lib):
         assert np.array_equal(W.bf16_bits(t["k_pool"]), kp) and np.array_equal(W.bf16_bits(t["v_pool"]), vp)
         ref = oracle_lib.attention(host["q"], kp, vp, b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale)
         check_close(widen(W.bf16_bits(out)), ref, b.name)
+
+
+def test_prefill_call_replays_from_a_hip_graph():
+    """The layer call enqueues kernels only (no allocation, no memset, no
+    synchronisation), so it can be captured once and replayed: every replay,
+    with eager work in between, reproduces the eager result bit for bit."""
+    b = W.make_custom_batch("graph", W.Geometry(8, 2, 128), [700, 64, 2300], [150, 80, 20], seed=31)
+    t = W.make_tensors(b, "cuda")
+    pools0 = (t["k_pool"].clone(), t["v_pool"].clone())
+    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, block_table=b.block_table, split_kv=3)
+    bt = torch.from_numpy(b.block_table).cuda()
+    ws = torch.empty(max(plan.prism_plan_workspace_bytes(), 256), dtype=torch.uint8, device="cuda")
+    eager = torch.full_like(t["q"], float("nan"))
+    plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], t["k_pool"], t["v_pool"], bt, eager, ws)
+    torch.cuda.synchronize()
+    pools_eager = (t["k_pool"].clone(), t["v_pool"].clone())
+    out = torch.full_like(t["q"], float("nan"))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        t["k_pool"].copy_(pools0[0]); t["v_pool"].copy_(pools0[1])
+        side.synchronize()
+        graph.capture_begin()
+        plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], t["k_pool"], t["v_pool"], bt, out, ws)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        t["k_pool"].copy_(pools0[0]); t["v_pool"].copy_(pools0[1])      # eager work between the replays
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+        assert torch.equal(t["k_pool"].view(torch.int16), pools_eager[0].view(torch.int16))
+        assert torch.equal(t["v_pool"].view(torch.int16), pools_eager[1].view(torch.int16))
+    plan.close()
