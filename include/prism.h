@@ -32,11 +32,15 @@
  *                     entries at or beyond ceil((P_r+S_r)/16) are never read
  *   prefix_len, suffix_len  int32 [batch], HOST memory, read at plan creation
  *
- * Ownership: the caller owns every buffer and the stream.  A plan owns a small
- * device allocation (its work lists), made by prism_plan_create on the current
- * device and released by prism_plan_destroy.  Split-KV partial results live in
- * the caller's workspace.  No entry point synchronises the device except
- * prism_plan_create / prism_plan_destroy / prism_plan_profile_read.
+ * Ownership: the caller owns every device buffer and the stream.  The library
+ * allocates no device memory and never waits for the device.  A plan is host
+ * memory; its work lists and the split-KV partial results live in the caller's
+ * workspace (prism_plan_workspace_bytes).  The first call that sees a
+ * workspace enqueues one asynchronous copy of the lists into its first bytes
+ * on the call's stream; later calls with the same workspace pointer reuse
+ * them, so the caller must leave those bytes alone between calls (or call
+ * prism_plan_forget_workspace).  prism_plan_destroy waits only for that copy;
+ * prism_plan_profile_read waits for the events it reads.
  *
  * Errors: every int-returning call gives PRISM_OK (0) or a negative PRISM_ERR_*
  * code; on error nothing has been enqueued.  Device-side block-table contents
@@ -55,7 +59,7 @@
 extern "C" {
 #endif
 
-#define PRISM_VERSION 100
+#define PRISM_VERSION 200
 
 enum {
   PRISM_OK = 0,
@@ -83,7 +87,9 @@ typedef struct prism_plan_options {
   int32_t tile_rows;           /* query rows per workgroup: 64, 128 or 256             */
   int32_t split_kv;            /* 0 auto, 1 never split, n>1 force n-way split         */
   int32_t min_split_keys;      /* auto split: smallest KV chunk, multiple of 64        */
-  int32_t reserved[5];
+  int32_t rows_per_wave;       /* query rows per wavefront: 32 or 64 (64 needs tile_rows
+                                  128 or 256: two or four waves, one per SIMD)         */
+  int32_t reserved[4];
   /* Optional HOST copy of the block table (int32 [batch][max_blocks_per_req]),
    * read only during plan creation.  Requests whose tables start with the same
    * page share a cached prefix (exact-prefix reuse, Eq. 3); the planner then
@@ -101,17 +107,19 @@ typedef struct prism_plan_info {
   int32_t num_split_items;     /* of those, how many write fp32 partials               */
   int32_t num_reduce_groups;   /* (request, kv head, row tile) groups merged afterwards*/
   int32_t total_suffix;        /* sum_S                                                */
-  int32_t reserved[2];
+  int32_t rows_per_wave;       /* query rows per wavefront: 32 or 64                   */
+  int32_t reserved[1];
   int64_t flops;               /* 4*d*Hq*sum_r(S_r*P_r + S_r(S_r+1)/2): unmasked pairs */
   int64_t kv_bytes_per_request;/* K and V bytes of every request's whole sequence      */
 } prism_plan_info_t;
 
 /*
- * Build the schedule for one wave geometry (host work: row tiles, longest-first
- * order, split-KV decisions, workspace offsets) and upload it.  The plan can be
+ * Build the schedule for one wave geometry (host work only: row tiles,
+ * longest-first order, split-KV decisions, workspace offsets).  The plan can be
  * reused for every layer of that wave.  prefix_len/suffix_len are HOST arrays of
  * shape->batch entries; S_r = 0 and P_r = 0 are both legal.  options may be NULL.
- * Synchronous (one small hipMalloc + hipMemcpy on the current device).
+ * Touches no device memory and enqueues nothing (the lists are kept in pinned
+ * host memory when a device is present, in plain host memory otherwise).
  */
 int prism_plan_create(const prism_shape_t *shape, const int32_t *prefix_len_host,
                       const int32_t *suffix_len_host, const prism_plan_options_t *options,
@@ -131,8 +139,14 @@ int prism_plan_dry_run(const prism_shape_t *shape, const int32_t *prefix_len_hos
                        int32_t items_capacity);
 
 /* Bytes of caller workspace that prism_prefix_prefill / prism_prefix_attention
- * need with this plan (0 when nothing is split). */
+ * need with this plan: the work lists, then the split-KV partial slots.  0 only
+ * for a plan without suffix tokens. */
 size_t prism_plan_workspace_bytes(const prism_plan_t *plan);
+
+/* Forget which workspace holds the plan's work lists: the next call uploads
+ * them again.  For callers that reuse the workspace memory for something else
+ * between calls. */
+int prism_plan_forget_workspace(prism_plan_t *plan);
 
 int prism_plan_get_info(const prism_plan_t *plan, prism_plan_info_t *out);
 
@@ -153,8 +167,9 @@ int prism_kv_append(const prism_plan_t *plan, const void *k_suffix, const void *
 /*
  * Attention only: the pools must already hold the suffix KV (for example from
  * prism_kv_append earlier on the same stream).  Writes out[sum_S][Hq][d].
- * workspace may be NULL when prism_plan_workspace_bytes is 0; it must be
- * 256-byte aligned.
+ * workspace is DEVICE memory, 256-byte aligned, of at least
+ * prism_plan_workspace_bytes (NULL only when that is 0).  Fails with
+ * PRISM_ERR_UNSUPPORTED on a device that is not gfx950 with 256 compute units.
  */
 int prism_prefix_attention(const prism_plan_t *plan, const void *q, const void *k_pool,
                            const void *v_pool, const int32_t *block_table_dev, void *out,

@@ -21,7 +21,8 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP, ERR_NO_MEMOR
 
 EXPORTS = (
     "prism_version", "prism_strerror", "prism_last_hip_error", "prism_plan_create",
-    "prism_plan_dry_run", "prism_plan_workspace_bytes", "prism_plan_get_info", "prism_plan_destroy", "prism_kv_append",
+    "prism_plan_dry_run", "prism_plan_workspace_bytes", "prism_plan_get_info", "prism_plan_forget_workspace",
+    "prism_plan_destroy", "prism_kv_append",
     "prism_prefix_attention", "prism_prefix_prefill", "prism_validate",
     "prism_plan_profile_enable", "prism_plan_profile_read", "prism_measure_peaks",
 )
@@ -46,7 +47,8 @@ class Shape(ctypes.Structure):
 
 class PlanOptions(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("split_kv", ctypes.c_int32),
-                ("min_split_keys", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5),
+                ("min_split_keys", ctypes.c_int32), ("rows_per_wave", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 4),
                 ("block_table_host", ctypes.c_void_p)]
 
 
@@ -54,7 +56,7 @@ class PlanInfo(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("tile_keys", ctypes.c_int32),
                 ("num_items", ctypes.c_int32), ("num_split_items", ctypes.c_int32),
                 ("num_reduce_groups", ctypes.c_int32), ("total_suffix", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2), ("flops", ctypes.c_int64),
+                ("rows_per_wave", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1), ("flops", ctypes.c_int64),
                 ("kv_bytes_per_request", ctypes.c_int64)]
 
 
@@ -90,6 +92,8 @@ def load():
     lib.prism_plan_workspace_bytes.argtypes = [vp]
     lib.prism_plan_get_info.restype = ctypes.c_int
     lib.prism_plan_get_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+    lib.prism_plan_forget_workspace.restype = ctypes.c_int
+    lib.prism_plan_forget_workspace.argtypes = [vp]
     lib.prism_plan_destroy.restype = None
     lib.prism_plan_destroy.argtypes = [vp]
     lib.prism_kv_append.restype = ctypes.c_int
@@ -124,6 +128,25 @@ def _ptr(t) -> Optional[int]:
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _check(name, t, dtype, numel, optional=False):
+    """The C ABI takes bare pointers: refuse a tensor that is not what the plan
+    was made for (device, dtype, contiguity, element count) before it gets there."""
+    import torch
+    if t is None:
+        if optional or numel == 0:
+            return
+        raise ValueError(f"{name}: missing")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    want = {"bf16": torch.bfloat16, "i32": torch.int32, "u8": torch.uint8}[dtype]
+    if t.dtype != want:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {want}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: {t.numel()} elements, the plan needs {numel}")
+
+
 def _stream() -> ctypes.c_void_p:
     import torch
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
@@ -140,9 +163,9 @@ def prism_validate(shape: Shape, prefix_len, suffix_len, block_table) -> int:
     return int(load().prism_validate(ctypes.byref(shape), pl.ctypes.data, sl.ctypes.data, bt.ctypes.data))
 
 
-def _options(tile_rows, split_kv, min_split_keys, block_table):
+def _options(tile_rows, split_kv, min_split_keys, block_table, rows_per_wave=0):
     """PlanOptions plus the host array it points to (keep both alive during the call)."""
-    opt = PlanOptions(tile_rows, split_kv, min_split_keys)
+    opt = PlanOptions(tile_rows, split_kv, min_split_keys, rows_per_wave)
     bt = None
     if block_table is not None:
         bt = _host_i32(block_table)
@@ -151,11 +174,11 @@ def _options(tile_rows, split_kv, min_split_keys, block_table):
 
 
 def prism_plan_dry_run(shape: Shape, prefix_len, suffix_len, tile_rows: int = 0, split_kv: int = 0,
-                       min_split_keys: int = 0, block_table=None):
+                       min_split_keys: int = 0, block_table=None, rows_per_wave: int = 0):
     """Host-only schedule: returns (PlanInfo, workspace_bytes, items int32 [n, 8])."""
     lib = load()
     pl, sl = _host_i32(prefix_len), _host_i32(suffix_len)
-    opt, _bt = _options(tile_rows, split_kv, min_split_keys, block_table)
+    opt, _bt = _options(tile_rows, split_kv, min_split_keys, block_table, rows_per_wave)
     info, ws = PlanInfo(), ctypes.c_size_t()
     n = lib.prism_plan_dry_run(ctypes.byref(shape), pl.ctypes.data, sl.ctypes.data, ctypes.byref(opt),
                                ctypes.byref(info), ctypes.byref(ws), None, 0)
@@ -172,7 +195,7 @@ class Plan:
     """Owns a prism_plan_t*.  Methods are the C entry points of the same name."""
 
     def __init__(self, shape: Shape, prefix_len, suffix_len, tile_rows: int = 0, split_kv: int = 0,
-                 min_split_keys: int = 0, block_table=None):
+                 min_split_keys: int = 0, block_table=None, rows_per_wave: int = 0):
         lib = load()
         self._lib = lib
         self._h = ctypes.c_void_p()
@@ -180,7 +203,10 @@ class Plan:
         pl, sl = _host_i32(prefix_len), _host_i32(suffix_len)
         if pl.shape != (shape.batch,) or sl.shape != (shape.batch,):
             raise ValueError("prefix_len/suffix_len must have `batch` entries")
-        opt, _bt = _options(tile_rows, split_kv, min_split_keys, block_table)
+        if block_table is not None and tuple(np.shape(block_table)) != (shape.batch, shape.max_blocks_per_req):
+            raise ValueError("block_table must be [batch, max_blocks_per_req]")
+        opt, _bt = _options(tile_rows, split_kv, min_split_keys, block_table, rows_per_wave)
+        self._total_suffix = int(sl.sum())
         rc = lib.prism_plan_create(ctypes.byref(shape), pl.ctypes.data, sl.ctypes.data,
                                    ctypes.byref(opt), ctypes.byref(self._h))
         if rc != PRISM_OK:
@@ -205,13 +231,34 @@ class Plan:
             raise PrismError(rc, "prism_plan_get_info")
         return info
 
+    def prism_plan_forget_workspace(self):
+        self._lib.prism_plan_forget_workspace(self._h)
+
+    def _check_call(self, q, k_suffix, v_suffix, k_pool, v_pool, block_table, out, workspace):
+        sh, n = self.shape, self._total_suffix
+        row_q, row_kv = sh.num_q_heads * sh.head_dim, sh.num_kv_heads * sh.head_dim
+        if q is not False:
+            _check("q", q, "bf16", n * row_q)
+            _check("out", out, "bf16", n * row_q)
+            _check("workspace", workspace, "u8", self.prism_plan_workspace_bytes())
+        if k_suffix is not False:
+            _check("k_suffix", k_suffix, "bf16", n * row_kv)
+            _check("v_suffix", v_suffix, "bf16", n * row_kv)
+        pool = sh.num_pages * sh.page_size * row_kv
+        _check("k_pool", k_pool, "bf16", pool)
+        _check("v_pool", v_pool, "bf16", pool)
+        _check("block_table", block_table, "i32", sh.batch * sh.max_blocks_per_req)
+
     def prism_kv_append(self, k_suffix, v_suffix, k_pool, v_pool, block_table):
+        self._check_call(False, k_suffix, v_suffix, k_pool, v_pool, block_table, None, None)
         rc = self._lib.prism_kv_append(self._h, _ptr(k_suffix), _ptr(v_suffix), _ptr(k_pool),
                                        _ptr(v_pool), _ptr(block_table), _stream())
         if rc != PRISM_OK:
             raise PrismError(rc, "prism_kv_append")
 
     def prism_prefix_attention(self, q, k_pool, v_pool, block_table, out, workspace=None):
+        if workspace is not None and workspace.numel() >= self.prism_plan_workspace_bytes():
+            self._check_call(q, False, False, k_pool, v_pool, block_table, out, workspace)   # size errors come from the library
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         rc = self._lib.prism_prefix_attention(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool),
                                               _ptr(block_table), _ptr(out), _ptr(workspace),
@@ -221,6 +268,8 @@ class Plan:
 
     def prism_prefix_prefill(self, q, k_suffix, v_suffix, k_pool, v_pool, block_table, out,
                              workspace=None):
+        if workspace is not None and workspace.numel() >= self.prism_plan_workspace_bytes():
+            self._check_call(q, k_suffix, v_suffix, k_pool, v_pool, block_table, out, workspace)
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         rc = self._lib.prism_prefix_prefill(self._h, _ptr(q), _ptr(k_suffix), _ptr(v_suffix),
                                             _ptr(k_pool), _ptr(v_pool), _ptr(block_table),

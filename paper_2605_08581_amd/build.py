@@ -10,9 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprism.so")
-SOURCES = ["prism_plan.cpp", "prism_api.cpp", "prism_sched.cpp", "prism_kernels.hip"]
+SOURCES = ["prism_plan.cpp", "prism_api.cpp", "prism_sched.cpp", "prism_kernels.hip", "prism_attn64.hip"]
 # packed fp32 VALU ops stay off: the kernels are written as ordinary float code
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -1,8 +1,17 @@
 // C ABI of the library: argument checks, plan lifetime, stream-ordered launches.
+//
+// The library allocates no device memory and never waits for the device.  A
+// plan keeps its work lists in host memory (pinned when the runtime allows);
+// they travel to the device in the first bytes of the caller's workspace, with
+// one asynchronous copy on the caller's stream the first time a call sees a
+// workspace (and again only when the caller hands in a different one).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -19,34 +28,116 @@ int hip_fail(hipError_t e, const char *what) {
   g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
   return PRISM_ERR_HIP;
 }
+int fail_with(int code, const char *what) {
+  g_hip_error = what;
+  return code;
+}
 
 struct EventPair {
   hipEvent_t a, b;
   int kind;   // 0 append, 1 attention, 2 reduce
 };
 
+constexpr size_t kMaxPendingTimings = 1 << 16;   // event pairs kept until prism_plan_profile_read
+std::atomic<uint64_t> g_plan_serial{1};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Pinned host memory for the plans' work lists.  Releasing pinned memory makes
+// the runtime wait for every stream of the device, so blocks are never handed
+// back to it: a destroyed plan's block goes on a free list (by power-of-two
+// size class) and the next plan of that class takes it.  Falls back to plain
+// host memory when nothing can be pinned (no device: host-only use).
+struct PinnedPool {
+  std::mutex mu;
+  std::vector<void *> free_blocks[40];
+  static int size_class(size_t bytes) {
+    int c = 12;                                   // 4 KiB and up
+    while (((size_t)1 << c) < bytes) ++c;
+    return c;
+  }
+  void *take(size_t bytes, bool *pinned, size_t *capacity) {
+    const int c = size_class(bytes);
+    *capacity = (size_t)1 << c;
+    {
+      std::lock_guard<std::mutex> lock(mu);
+      if (!free_blocks[c].empty()) {
+        void *p = free_blocks[c].back();
+        free_blocks[c].pop_back();
+        *pinned = true;
+        return p;
+      }
+    }
+    void *p = nullptr;
+    if (hipHostMalloc(&p, *capacity, hipHostMallocDefault) == hipSuccess && p) {
+      *pinned = true;
+      return p;
+    }
+    (void)hipGetLastError();                      // the failed attempt is ours: do not leave it for the caller
+    *pinned = false;
+    return std::malloc(*capacity);
+  }
+  void give_back(void *p, bool pinned, size_t capacity) {
+    if (!p) return;
+    if (!pinned) {
+      std::free(p);
+      return;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    free_blocks[size_class(capacity)].push_back(p);
+  }
+};
+PinnedPool g_pinned;
+
+// Machine shape the planner's placement assumes, checked once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_dev_mu;
+int g_dev_ok[kMaxDevices] = {};                  // 0 unknown, 1 fine, -1 not the expected chip
+
+int check_device() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail_with(PRISM_ERR_UNSUPPORTED, "device index out of range");
+  std::lock_guard<std::mutex> lock(g_dev_mu);
+  if (g_dev_ok[dev] == 0) {
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDeviceProperties");
+    const bool arch_ok = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+    g_dev_ok[dev] = (arch_ok && prop.multiProcessorCount == kNumCU) ? 1 : -1;
+  }
+  if (g_dev_ok[dev] < 0)
+    return fail_with(PRISM_ERR_UNSUPPORTED,
+                     "the kernels and the planner's die-aware order are built for gfx950 with 256 compute units");
+  return PRISM_OK;
+}
+
 }  // namespace
 
 struct prism_plan {
   prism_shape_t shape;
   Schedule sch;
-  int device = 0;
-  void *dev_blob = nullptr;
-  AttnItem *d_items = nullptr;
-  ReduceGroup *d_groups = nullptr;
-  TokInfo *d_toks = nullptr;
   float scale_log2e = 0.f;
-  // profiling
-  bool profiling = false;
-  std::vector<EventPair> pending;
-  std::vector<hipEvent_t> free_events;
+  uint64_t serial = 0;
+  // work lists as the kernels read them: [items | groups], then the partial slots
+  unsigned char *host_lists = nullptr;
+  bool host_pinned = false;
+  size_t host_capacity = 0;
+  size_t items_bytes = 0, lists_bytes = 0, total_bytes = 0;
+  std::vector<AppendChunk> append_chunks;
+  std::vector<int> append_max_suffix;
+  // state that calls on a const plan update
+  mutable const void *lists_in = nullptr;        // workspace that holds the lists (nullptr: none yet)
+  mutable hipEvent_t upload_done = nullptr;      // after the last upload: destroy waits for it, not for the device
+  mutable bool profiling = false;
+  mutable std::vector<EventPair> pending;
+  mutable std::vector<hipEvent_t> free_events;
 };
 
 namespace {
 
-size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-hipEvent_t take_event(prism_plan *p) {
+hipEvent_t take_event(const prism_plan *p) {
   if (!p->free_events.empty()) {
     hipEvent_t e = p->free_events.back();
     p->free_events.pop_back();
@@ -57,38 +148,50 @@ hipEvent_t take_event(prism_plan *p) {
   return e;
 }
 
+// Brackets one kernel with events when profiling is on; never while the
+// stream is being captured into a graph (events recorded there would belong
+// to the graph) and never beyond kMaxPendingTimings unread pairs.
 struct Timed {
-  prism_plan *p;
+  const prism_plan *p;
   hipStream_t st;
   EventPair ev{nullptr, nullptr, 0};
-  Timed(const prism_plan *plan, void *stream, int kind) : p(const_cast<prism_plan *>(plan)), st((hipStream_t)stream) {
-    if (!p->profiling) return;
+  bool on = false;
+  Timed(const prism_plan *plan, void *stream, int kind) : p(plan), st((hipStream_t)stream) {
+    if (!p->profiling || p->pending.size() >= kMaxPendingTimings) return;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) return;
     ev.a = take_event(p);
     ev.b = take_event(p);
     ev.kind = kind;
-    if (ev.a) (void)hipEventRecord(ev.a, st);
+    on = ev.a && ev.b;
+    if (on) (void)hipEventRecord(ev.a, st);
   }
   ~Timed() {
-    if (!p->profiling) return;
-    if (ev.b) (void)hipEventRecord(ev.b, st);
-    if (ev.a && ev.b) p->pending.push_back(ev);
+    if (!on) {
+      if (ev.a) p->free_events.push_back(ev.a);
+      if (ev.b) p->free_events.push_back(ev.b);
+      return;
+    }
+    (void)hipEventRecord(ev.b, st);
+    p->pending.push_back(ev);
   }
 };
 
 LaunchParams make_params(const prism_plan *p, const void *q, const void *k_pool, const void *v_pool,
-                         const int32_t *bt, void *out, void *workspace) {
+                         const int32_t *bt, void *out, unsigned char *lists_dev) {
   LaunchParams lp{};
   lp.q = q;
   lp.k_pool = k_pool;
   lp.v_pool = v_pool;
   lp.block_table = bt;
   lp.out = out;
-  lp.partials = (float *)workspace;
-  lp.items = p->d_items;
-  lp.groups = p->d_groups;
+  lp.items = (const AttnItem *)lists_dev;
+  lp.groups = (const ReduceGroup *)(lists_dev + p->items_bytes);
+  lp.partials = (float *)(lists_dev + p->lists_bytes);
   lp.num_items = (int)p->sch.items.size();
   lp.num_groups = (int)p->sch.groups.size();
   lp.tile_rows = p->sch.tile_rows;
+  lp.rows_per_wave = p->sch.rows_per_wave;
   lp.Hq = p->shape.num_q_heads;
   lp.Hkv = p->shape.num_kv_heads;
   lp.d = p->shape.head_dim;
@@ -101,17 +204,34 @@ int do_append(const prism_plan *plan, const void *k_suffix, const void *v_suffix
               void *v_pool, const int32_t *bt, void *stream) {
   if (plan->sch.total_suffix == 0) return PRISM_OK;
   Timed t(plan, stream, 0);
-  int e = launch_append(k_suffix, v_suffix, k_pool, v_pool, bt, plan->d_toks,
-                        (int)plan->sch.total_suffix, plan->shape.num_kv_heads, plan->shape.head_dim,
-                        plan->shape.max_blocks_per_req, stream);
-  if (e != 0) return hip_fail((hipError_t)e, "kv_append launch");
+  for (size_t c = 0; c < plan->append_chunks.size(); ++c) {
+    int e = launch_append(k_suffix, v_suffix, k_pool, v_pool, bt, plan->append_chunks[c],
+                          plan->append_max_suffix[c], plan->shape.num_kv_heads, plan->shape.head_dim,
+                          plan->shape.max_blocks_per_req, stream);
+    if (e != 0) return hip_fail((hipError_t)e, "kv_append launch");
+  }
+  return PRISM_OK;
+}
+
+// One asynchronous copy of the work lists into the first bytes of dst.
+int upload_lists(const prism_plan *plan, void *dst, void *stream) {
+  if (plan->lists_bytes == 0) return PRISM_OK;
+  hipError_t e = hipMemcpyAsync(dst, plan->host_lists, plan->lists_bytes, hipMemcpyHostToDevice,
+                                (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(plan work lists)");
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing((hipStream_t)stream, &cs) == hipSuccess && cs == hipStreamCaptureStatusNone) {
+    if (!plan->upload_done && hipEventCreateWithFlags(&plan->upload_done, hipEventDisableTiming) != hipSuccess)
+      plan->upload_done = nullptr;
+    if (plan->upload_done) (void)hipEventRecord(plan->upload_done, (hipStream_t)stream);
+  }
   return PRISM_OK;
 }
 
 int do_attention(const prism_plan *plan, const void *q, const void *k_pool, const void *v_pool,
-                 const int32_t *bt, void *out, void *workspace, void *stream) {
+                 const int32_t *bt, void *out, unsigned char *lists_dev, void *stream) {
   if (plan->sch.items.empty()) return PRISM_OK;
-  LaunchParams lp = make_params(plan, q, k_pool, v_pool, bt, out, workspace);
+  LaunchParams lp = make_params(plan, q, k_pool, v_pool, bt, out, lists_dev);
   {
     Timed t(plan, stream, 1);
     int e = launch_attention(lp, stream);
@@ -133,16 +253,32 @@ void fill_info(const Schedule &sch, prism_plan_info_t *out) {
   out->num_split_items = sch.num_split_items;
   out->num_reduce_groups = (int32_t)sch.groups.size();
   out->total_suffix = (int32_t)sch.total_suffix;
+  out->rows_per_wave = sch.rows_per_wave;
   out->flops = sch.flops;
   out->kv_bytes_per_request = sch.kv_bytes;
 }
 
+// Bytes of workspace: work lists (256-byte aligned parts), then partial slots.
+void layout_sizes(const Schedule &sch, size_t *items_b, size_t *lists_b, size_t *total_b) {
+  *items_b = align_up(sch.items.size() * sizeof(AttnItem), 256);
+  *lists_b = *items_b + align_up(sch.groups.size() * sizeof(ReduceGroup), 256);
+  *total_b = *lists_b + sch.workspace_bytes;
+}
+
 int check_workspace(const prism_plan *plan, const void *workspace, size_t bytes) {
-  if (plan->sch.workspace_bytes == 0) return PRISM_OK;
+  if (plan->total_bytes == 0) return PRISM_OK;
   if (!workspace) return PRISM_ERR_INVALID_ARG;
   if (((uintptr_t)workspace & 255u) != 0) return PRISM_ERR_INVALID_ARG;
-  if (bytes < plan->sch.workspace_bytes) return PRISM_ERR_WORKSPACE_TOO_SMALL;
+  if (bytes < plan->total_bytes) return PRISM_ERR_WORKSPACE_TOO_SMALL;
   return PRISM_OK;
+}
+
+// Lists into the caller's workspace unless they are there already.
+int ensure_lists(const prism_plan *plan, void *workspace, void *stream) {
+  if (plan->lists_bytes == 0 || plan->lists_in == workspace) return PRISM_OK;
+  int rc = upload_lists(plan, workspace, stream);
+  if (rc == PRISM_OK) plan->lists_in = workspace;
+  return rc;
 }
 
 }  // namespace
@@ -155,7 +291,7 @@ const char *prism_strerror(int code) {
   switch (code) {
     case PRISM_OK: return "ok";
     case PRISM_ERR_INVALID_ARG: return "invalid argument";
-    case PRISM_ERR_UNSUPPORTED: return "unsupported shape or option";
+    case PRISM_ERR_UNSUPPORTED: return "unsupported shape, option or device";
     case PRISM_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case PRISM_ERR_HIP: return "HIP runtime error";
     case PRISM_ERR_NO_MEMORY: return "out of memory";
@@ -180,6 +316,23 @@ int prism_plan_create(const prism_shape_t *shape, const int32_t *prefix_len_host
   int rc;
   try {
     rc = build_schedule(*shape, prefix_len_host, suffix_len_host, opt, &p->sch);
+    if (rc == PRISM_OK) {
+      for (int r0 = 0; r0 < shape->batch; r0 += kAppendChunk) {
+        AppendChunk c;
+        std::memset(&c, 0, sizeof c);
+        c.req0 = r0;
+        c.nreq = std::min(kAppendChunk, shape->batch - r0);
+        int longest = 0;
+        for (int i = 0; i < c.nreq; ++i) {
+          c.prefix[i] = prefix_len_host[r0 + i];
+          c.suffix[i] = suffix_len_host[r0 + i];
+          c.q_off[i] = p->sch.q_off[r0 + i];
+          longest = std::max(longest, c.suffix[i]);
+        }
+        p->append_chunks.push_back(c);
+        p->append_max_suffix.push_back(longest);
+      }
+    }
   } catch (const std::bad_alloc &) {
     rc = PRISM_ERR_NO_MEMORY;
   }
@@ -188,31 +341,19 @@ int prism_plan_create(const prism_shape_t *shape, const int32_t *prefix_len_host
     return rc;
   }
   p->scale_log2e = shape->softmax_scale * 1.4426950408889634f;
-
-  const size_t items_b = align_up(p->sch.items.size() * sizeof(AttnItem), 256);
-  const size_t groups_b = align_up(p->sch.groups.size() * sizeof(ReduceGroup), 256);
-  const size_t toks_b = align_up(p->sch.toks.size() * sizeof(TokInfo), 256);
-  const size_t total = items_b + groups_b + toks_b;
-  if (total > 0) {
-    hipError_t e = hipGetDevice(&p->device);
-    if (e != hipSuccess) { delete p; return hip_fail(e, "hipGetDevice"); }
-    e = hipMalloc(&p->dev_blob, total);
-    if (e != hipSuccess) { delete p; return hip_fail(e, "hipMalloc(plan work lists)"); }
-    char *base = (char *)p->dev_blob;
-    p->d_items = (AttnItem *)base;
-    p->d_groups = (ReduceGroup *)(base + items_b);
-    p->d_toks = (TokInfo *)(base + items_b + groups_b);
-    if (!p->sch.items.empty())
-      e = hipMemcpy(p->d_items, p->sch.items.data(), p->sch.items.size() * sizeof(AttnItem), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !p->sch.groups.empty())
-      e = hipMemcpy(p->d_groups, p->sch.groups.data(), p->sch.groups.size() * sizeof(ReduceGroup), hipMemcpyHostToDevice);
-    if (e == hipSuccess && !p->sch.toks.empty())
-      e = hipMemcpy(p->d_toks, p->sch.toks.data(), p->sch.toks.size() * sizeof(TokInfo), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-      (void)hipFree(p->dev_blob);
+  p->serial = g_plan_serial.fetch_add(1);
+  layout_sizes(p->sch, &p->items_bytes, &p->lists_bytes, &p->total_bytes);
+  if (p->lists_bytes > 0) {
+    // pinned, so that the upload is a true asynchronous copy
+    void *h = g_pinned.take(p->lists_bytes, &p->host_pinned, &p->host_capacity);
+    if (!h) {
       delete p;
-      return hip_fail(e, "hipMemcpy(plan work lists)");
+      return PRISM_ERR_NO_MEMORY;
     }
+    p->host_lists = (unsigned char *)h;
+    std::memset(h, 0, p->lists_bytes);
+    std::memcpy(h, p->sch.items.data(), p->sch.items.size() * sizeof(AttnItem));
+    std::memcpy(p->host_lists + p->items_bytes, p->sch.groups.data(), p->sch.groups.size() * sizeof(ReduceGroup));
   }
   *out_plan = p;
   return PRISM_OK;
@@ -235,7 +376,11 @@ int prism_plan_dry_run(const prism_shape_t *shape, const int32_t *prefix_len_hos
   }
   if (rc != PRISM_OK) return rc;
   if (info) fill_info(sch, info);
-  if (workspace_bytes) *workspace_bytes = sch.workspace_bytes;
+  if (workspace_bytes) {
+    size_t items_b, lists_b, total_b;
+    layout_sizes(sch, &items_b, &lists_b, &total_b);
+    *workspace_bytes = total_b;
+  }
   if (items_out) {
     for (size_t i = 0; i < sch.items.size() && (int32_t)i < items_capacity; ++i) {
       const AttnItem &it = sch.items[i];   // idle padding entries have req = -1
@@ -247,7 +392,7 @@ int prism_plan_dry_run(const prism_shape_t *shape, const int32_t *prefix_len_hos
   return (int)sch.items.size();
 }
 
-size_t prism_plan_workspace_bytes(const prism_plan_t *plan) { return plan ? plan->sch.workspace_bytes : 0; }
+size_t prism_plan_workspace_bytes(const prism_plan_t *plan) { return plan ? plan->total_bytes : 0; }
 
 int prism_plan_get_info(const prism_plan_t *plan, prism_plan_info_t *out) {
   if (!plan || !out) return PRISM_ERR_INVALID_ARG;
@@ -255,15 +400,25 @@ int prism_plan_get_info(const prism_plan_t *plan, prism_plan_info_t *out) {
   return PRISM_OK;
 }
 
+int prism_plan_forget_workspace(prism_plan_t *plan) {
+  if (!plan) return PRISM_ERR_INVALID_ARG;
+  plan->lists_in = nullptr;
+  return PRISM_OK;
+}
+
 void prism_plan_destroy(prism_plan_t *plan) {
   if (!plan) return;
-  if (plan->dev_blob || !plan->pending.empty() || !plan->free_events.empty()) (void)hipDeviceSynchronize();
+  // the only device work that reads plan-owned memory is the list upload
+  if (plan->upload_done) {
+    (void)hipEventSynchronize(plan->upload_done);
+    (void)hipEventDestroy(plan->upload_done);
+  }
   for (auto &ev : plan->pending) {
     (void)hipEventDestroy(ev.a);
     (void)hipEventDestroy(ev.b);
   }
   for (auto e : plan->free_events) (void)hipEventDestroy(e);
-  if (plan->dev_blob) (void)hipFree(plan->dev_blob);
+  g_pinned.give_back(plan->host_lists, plan->host_pinned, plan->host_capacity);
   delete plan;
 }
 
@@ -281,7 +436,12 @@ int prism_prefix_attention(const prism_plan_t *plan, const void *q, const void *
   if (plan->sch.total_suffix > 0 && (!q || !out)) return PRISM_ERR_INVALID_ARG;
   int rc = check_workspace(plan, workspace, workspace_bytes);
   if (rc != PRISM_OK) return rc;
-  return do_attention(plan, q, k_pool, v_pool, block_table_dev, out, workspace, hip_stream);
+  if (plan->sch.items.empty()) return PRISM_OK;
+  rc = check_device();
+  if (rc != PRISM_OK) return rc;
+  rc = ensure_lists(plan, workspace, hip_stream);
+  if (rc != PRISM_OK) return rc;
+  return do_attention(plan, q, k_pool, v_pool, block_table_dev, out, (unsigned char *)workspace, hip_stream);
 }
 
 int prism_prefix_prefill(const prism_plan_t *plan, const void *q, const void *k_suffix,
@@ -292,9 +452,14 @@ int prism_prefix_prefill(const prism_plan_t *plan, const void *q, const void *k_
   if (plan->sch.total_suffix > 0 && (!q || !out || !k_suffix || !v_suffix)) return PRISM_ERR_INVALID_ARG;
   int rc = check_workspace(plan, workspace, workspace_bytes);
   if (rc != PRISM_OK) return rc;
+  if (plan->sch.total_suffix == 0) return PRISM_OK;
+  rc = check_device();
+  if (rc != PRISM_OK) return rc;
+  rc = ensure_lists(plan, workspace, hip_stream);
+  if (rc != PRISM_OK) return rc;
   rc = do_append(plan, k_suffix, v_suffix, k_pool, v_pool, block_table_dev, hip_stream);
   if (rc != PRISM_OK) return rc;
-  return do_attention(plan, q, k_pool, v_pool, block_table_dev, out, workspace, hip_stream);
+  return do_attention(plan, q, k_pool, v_pool, block_table_dev, out, (unsigned char *)workspace, hip_stream);
 }
 
 int prism_validate(const prism_shape_t *shape, const int32_t *prefix_len_host,

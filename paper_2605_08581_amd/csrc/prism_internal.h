@@ -43,19 +43,26 @@ struct ReduceGroup {
 };
 static_assert(sizeof(ReduceGroup) == 32, "ReduceGroup is 32 bytes");
 
-// One suffix token for the append kernel.
-struct TokInfo {
-  int32_t req;
-  int32_t pos;         // absolute position P_r + i
+// The append kernel takes the lengths of up to kAppendChunk requests by value
+// (kernel arguments), so it needs no work list in device memory.
+constexpr int kAppendChunk = 256;
+struct AppendChunk {
+  int32_t prefix[kAppendChunk];   // P_r
+  int32_t suffix[kAppendChunk];   // S_r
+  int32_t q_off[kAppendChunk];    // first row of the request in k_suffix / v_suffix
+  int32_t req0;                   // request index of entry 0
+  int32_t nreq;
 };
+static_assert(sizeof(AppendChunk) <= 3584, "the chunk travels in the kernel argument segment");
 
 struct KernelTimes;    // defined in prism_api.cpp
 
 struct Schedule {
   int tile_rows = 128;
+  int rows_per_wave = 32;
   std::vector<AttnItem> items;
   std::vector<ReduceGroup> groups;
-  std::vector<TokInfo> toks;
+  std::vector<int32_t> q_off;   // per request: first row in the packed q / k_suffix / v_suffix arrays
   int num_split_items = 0;
   int num_slots = 0;           // partial slots in the workspace
   size_t workspace_bytes = 0;
@@ -89,13 +96,15 @@ struct LaunchParams {
   int num_items;
   int num_groups;
   int tile_rows;
+  int rows_per_wave;
   int Hq, Hkv, d, max_blocks;
   float scale_log2e;
 };
 int launch_attention(const LaunchParams &p, void *stream);
+int launch_attention64(const LaunchParams &p, void *stream);   // 64 rows per wave (prism_attn64.hip)
 int launch_reduce(const LaunchParams &p, void *stream);
 int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_pool,
-                  const int32_t *block_table, const TokInfo *toks, int num_tokens, int Hkv, int d,
+                  const int32_t *block_table, const AppendChunk &chunk, int max_suffix, int Hkv, int d,
                   int max_blocks, void *stream);
 
 int launch_mfma_peak(float *sink, int iters, int *waves, void *stream);

@@ -4,64 +4,53 @@
 // What is computed follows the paper's statement of prefix reuse (Sec. 2.2,
 // Eq. 3-4): the uncached suffix rows of each request attend causally over the
 // cached prefix KV (gathered through the block table) and over their own KV.
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-
-#include <type_traits>
-
-#include "prism_internal.h"
+#include "prism_device.h"
 
 namespace prism {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
 // --------------------------------------------------------------------------
-// Paged KV append.  One thread moves 16 bytes of K and 16 bytes of V.
+// Paged KV append.  One thread moves 16 bytes of K and 16 bytes of V.  Block
+// row y of the grid serves request req0 + y of the chunk; its prefix, suffix
+// and source offset arrive in the kernel arguments.
 // --------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(
     const u32x4 *__restrict__ k_src, const u32x4 *__restrict__ v_src, u32x4 *__restrict__ k_pool,
-    u32x4 *__restrict__ v_pool, const int32_t *__restrict__ block_table,
-    const TokInfo *__restrict__ toks, int num_tokens, int Hkv, int max_blocks) {
+    u32x4 *__restrict__ v_pool, const int32_t *__restrict__ block_table, const AppendChunk chunk,
+    int Hkv, int max_blocks) {
   constexpr int CH = D / 8;                       // 16-byte chunks per (token, head) row
-  const int64_t per_tok = (int64_t)Hkv * CH;
-  const int64_t total = (int64_t)num_tokens * per_tok;
-  for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < total;
-       c += (int64_t)gridDim.x * blockDim.x) {
-    const int tok = (int)(c / per_tok);
-    const int rem = (int)(c - (int64_t)tok * per_tok);
+  const int y = blockIdx.y;
+  const int S = chunk.suffix[y], P = chunk.prefix[y];
+  const int per_tok = Hkv * CH;
+  const int total = S * per_tok;                  // < 2^31: checked at plan creation
+  const int32_t *bt = block_table + (int64_t)(chunk.req0 + y) * max_blocks;
+  const int64_t src0 = (int64_t)chunk.q_off[y] * per_tok;
+  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < total; c += gridDim.x * blockDim.x) {
+    const int tok = c / per_tok;
+    const int rem = c - tok * per_tok;
     const int h = rem / CH, ch = rem % CH;
-    const TokInfo ti = toks[tok];
-    const int32_t page = block_table[(int64_t)ti.req * max_blocks + ti.pos / kPage];
-    const int64_t dst = (((int64_t)page * Hkv + h) * kPage + (ti.pos % kPage)) * CH + ch;
-    k_pool[dst] = k_src[c];
-    v_pool[dst] = v_src[c];
+    const int pos = P + tok;
+    const int32_t page = bt[pos / kPage];
+    const int64_t dst = (((int64_t)page * Hkv + h) * kPage + (pos % kPage)) * CH + ch;
+    k_pool[dst] = k_src[src0 + c];
+    v_pool[dst] = v_src[src0 + c];
   }
 }
 
 int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_pool,
-                  const int32_t *block_table, const TokInfo *toks, int num_tokens, int Hkv, int d,
+                  const int32_t *block_table, const AppendChunk &chunk, int max_suffix, int Hkv, int d,
                   int max_blocks, void *stream) {
-  if (num_tokens == 0) return 0;
-  const int64_t total = (int64_t)num_tokens * Hkv * (d / 8);
-  int64_t blocks = (total + 255) / 256;
-  if (blocks > 16 * 1024) blocks = 16 * 1024;
-  dim3 grid((unsigned)blocks), block(256);
+  if (chunk.nreq == 0 || max_suffix == 0) return 0;
+  const int64_t longest = (int64_t)max_suffix * Hkv * (d / 8);
+  int64_t bx = (longest + 255) / 256;
+  if (bx > 1024) bx = 1024;                       // longer requests loop
+  const dim3 grid((unsigned)bx, (unsigned)chunk.nreq), block(256);
   hipStream_t st = (hipStream_t)stream;
   if (d == 128)
-    hipLaunchKernelGGL(kv_append_kernel<128>, grid, block, 0, st, (const u32x4 *)k_src,
-                       (const u32x4 *)v_src, (u32x4 *)k_pool, (u32x4 *)v_pool, block_table, toks,
-                       num_tokens, Hkv, max_blocks);
-  else
-    hipLaunchKernelGGL(kv_append_kernel<64>, grid, block, 0, st, (const u32x4 *)k_src,
-                       (const u32x4 *)v_src, (u32x4 *)k_pool, (u32x4 *)v_pool, block_table, toks,
-                       num_tokens, Hkv, max_blocks);
-  return (int)hipGetLastError();
+    return launch_kernel(kv_append_kernel<128>, grid, block, 0, st, (const u32x4 *)k_src, (const u32x4 *)v_src,
+                         (u32x4 *)k_pool, (u32x4 *)v_pool, block_table, chunk, Hkv, max_blocks);
+  return launch_kernel(kv_append_kernel<64>, grid, block, 0, st, (const u32x4 *)k_src, (const u32x4 *)v_src,
+                       (u32x4 *)k_pool, (u32x4 *)v_pool, block_table, chunk, Hkv, max_blocks);
 }
 
 // --------------------------------------------------------------------------
@@ -99,71 +88,6 @@ int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_po
 // the final division by the row sum cancels the offset exactly, and the
 // accumulator rescale is skipped on almost every tile.
 // --------------------------------------------------------------------------
-
-template <int D>
-__device__ __forceinline__ int swz(int key) {
-  if (D == 128) return ((key & 3) << 2) | ((key >> 2) & 3);
-  return (((key >> 1) & 1) << 2) | ((key >> 2) & 3);
-}
-
-template <int D>
-__device__ __forceinline__ int lds_off(int key, int chunk) {   // byte offset of a 16-byte chunk
-  return key * (D * 2) + ((chunk ^ swz<D>(key)) << 4);
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// max over the two 32-lane halves of a wave, result in every lane
-__device__ __forceinline__ float max_across_halves(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float sum_across_halves(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane l's data lands
-// at lds_base + 16*l (lds_base is wave-uniform and travels in M0).  The source
-// is a buffer resource (wave-uniform base of one (page, head) block, in scalar
-// registers) plus a per-lane byte offset, which keeps all address arithmetic
-// off the vector ALU and makes a stray offset read zeros instead of faulting.
-// Inline assembly, so that the compiler does not make later LDS reads of
-// *other* slots wait for these copies; the kernel waits for them itself
-// (s_waitcnt vmcnt(0), then a workgroup barrier) before a slot is read.
-typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
-__device__ __forceinline__ i32x4 block_resource(const void *base, uint32_t bytes) {
-  const uint64_t a = (uint64_t)(uintptr_t)base;
-  i32x4 r;
-  r[0] = (int32_t)(uint32_t)a;
-  r[1] = (int32_t)(uint32_t)((a >> 32) & 0xFFFFu);   // stride 0: a raw byte buffer
-  r[2] = (int32_t)bytes;                             // offsets at or past this read as zero
-  r[3] = 0x00020000;                                 // 32-bit untyped data
-  return r;
-}
-__device__ __forceinline__ void copy16_to_lds(i32x4 rsrc, uint32_t lane_off, uint32_t lds_base) {
-  __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %0, 0 offen lds"
-                   :
-                   : "s"(rsrc), "v"(lane_off), "s"(lds_base)
-                   : "memory");
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-
-constexpr float kRescaleThreshold = 8.0f;   // log2 units
-
-
-// f(integral_constant<int, B>) ... f(integral_constant<int, E-1>), expanded at
-// compile time: the body sees its index as a constant expression.
-template <int B, int E, class F>
-__device__ __forceinline__ void static_for(F &&f) {
-  if constexpr (B < E) {
-    f(std::integral_constant<int, B>{});
-    static_for<B + 1, E>(f);
-  }
-}
 
 template <int D, int RB, int NW, int WPE, int NS>
 __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
@@ -371,6 +295,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       grow |= (mx[rb] - m_run[rb]) * scale_log2e > kRescaleThreshold;
     }
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      if constexpr (RB > 1) mfma_drain();
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         const float m_new = fmaxf(m_run[rb], mx[rb]);
@@ -382,6 +307,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[db][rb][r] *= alpha;
       }
+      if constexpr (RB > 1) __asm__ volatile("s_nop 1");
     }
   };
   // P^T fragment of k-step ks from the scores (exp2, row sums, bf16 rounding)
@@ -438,8 +364,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       for (int db = 0; db < DB; ++db) {
         const bf16x8 a = v_frag(v_cur, ks * DB + db);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          oacc[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb], oacc[db][rb], 0, 0, 0);
+        for (int rb = 0; rb < RB; ++rb) pv_mfma<(RB > 1)>(oacc[db][rb], a, pf[rb]);
       }
     }
   };
@@ -455,51 +380,62 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   // burst before the step: a copy instruction that finds the load queue full
   // then holds up one wave for a moment rather than every wave of the
   // workgroup at once, and the data still has most of an iteration to arrive.
-  constexpr int NQK = KB * KK;                    // S^T MFMAs per tile (per row block)
-  constexpr int NPV = KS * DB;                    // O^T MFMAs per tile
+  constexpr int NQK = KB * KK;                    // K fragments per tile (one S^T MFMA each per row block)
+  constexpr int NPV = KS * DB;                    // V^T fragments per tile (one O^T MFMA each per row block)
   constexpr int NEL = KB * 16;                    // score elements per lane per row block
-  constexpr int LA = 3;                           // fragment reads run this many chunks ahead
-  constexpr int CSPAN = NQK + (KS - 1) * DB;      // chunks over which the exponentials spread
+  constexpr int LA = 3;                           // fragment reads run this many fragments ahead
+  constexpr int NCH = (NQK + NPV) * RB;           // chunks (= MFMAs) per step
+  constexpr int CSPAN = (NQK + (KS - 1) * DB) * RB;   // chunks over which the exponentials spread
   auto step = [&](f32x16 (&sc)[KB][RB], f32x16 (&sn)[KB][RB], uint32_t k_next, uint32_t v_cur,
                   int next_key0, auto mask_tag, auto vslot_tag, auto kslot_tag) __attribute__((always_inline)) {
     constexpr int VSLOT = decltype(vslot_tag)::value, KSLOT = decltype(kslot_tag)::value;
     constexpr int NC = 2 * UPW;
-    constexpr int STRIDE = 2 * NC <= NQK + NPV ? 2 : 1;   // every other chunk from the start of the step
-    static_assert(RB == 1, "the overlapped step is written for one 32-row block per wave");
-    const float mc = m_run[0] * scale_log2e;
-    float sum_even = 0.f, sum_odd = 0.f;          // two chains: no add waits on the one before it
+    constexpr int STRIDE = 2 * NC <= NCH ? 2 : 1;   // every other chunk from the start of the step
+    float mc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) mc[rb] = m_run[rb] * scale_log2e;
+    float sum_even[RB], sum_odd[RB];              // two chains per row: no add waits on the one before it
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) sum_even[rb] = sum_odd[rb] = 0.f;
     bf16x8 frag[LA + 1];                          // ring of K / V^T fragments in flight
-    bf16x8 pf[KS];                                // P^T fragments, one per 16-key k-step
+    bf16x8 pf[KS][RB];                            // P^T fragments, one per 16-key k-step and row block
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sn[kb][0][r] = 0.f;
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sn[kb][rb][r] = 0.f;
     auto fetch = [&](int i) {                     // fragment i of the chain: K first, then V^T
       if (i < NQK) frag[i % (LA + 1)] = k_frag(k_next, i);
       else if (i < NQK + NPV) frag[i % (LA + 1)] = v_frag(v_cur, i - NQK);
     };
     // Softmax of the current tile, spread over the chunks as a three-stage
-    // pipeline so that no chunk waits on its own results: element e has its
-    // exponent argument formed in chunk home(e)-1, exp2 taken in chunk
-    // home(e), and is rounded to bf16 (two at a time) and added to the row sum
-    // in chunk home(e)+1.  The row sum adds the fp32 exponentials (before the
-    // rounding): plain adds on two alternating chains measured 2 % faster over
-    // the whole kernel than a packed dot product of the rounded pairs, and the
-    // difference to the rounded sum is far inside the tolerance.
-    auto home = [](int e) { return 1 + (e * (CSPAN - 2)) / NEL; };
+    // pipeline so that no chunk waits on its own results.  The elements are
+    // walked in the order the O^T MFMAs consume them (k-step, row block, key);
+    // element x has its exponent argument formed in chunk home(x)-1, exp2
+    // taken in chunk home(x), and is rounded to bf16 (two at a time) and added
+    // to the row sum in chunk home(x)+1.  The row sum adds the fp32
+    // exponentials (before the rounding): plain adds on two alternating chains
+    // measured 2 % faster over the whole kernel than a packed dot product of
+    // the rounded pairs, and the difference to the rounded sum is far inside
+    // the tolerance.
+    constexpr int NX = NEL * RB;
+    auto home = [](int x) { return 1 + (x * (CSPAN - 2)) / NX; };
     auto softmax_slice = [&](int c) {
 #pragma unroll
-      for (int e = 0; e < NEL; ++e) {
-        if (home(e) == c + 1) sc[e / 16][0][e % 16] = fmaf(sc[e / 16][0][e % 16], scale_log2e, -mc);
-        if (home(e) == c) sc[e / 16][0][e % 16] = fast_exp2(sc[e / 16][0][e % 16]);
-        if ((e & 1) && home(e) == c - 1) {
+      for (int x = 0; x < NX; ++x) {
+        const int ks = x / (8 * RB), rb = (x / 8) % RB, e8 = x % 8;
+        const int e = 8 * ks + e8;                // element of the row block's tile column
+        if (home(x) == c + 1) sc[e / 16][rb][e % 16] = fmaf(sc[e / 16][rb][e % 16], scale_log2e, -mc[rb]);
+        if (home(x) == c) sc[e / 16][rb][e % 16] = fast_exp2(sc[e / 16][rb][e % 16]);
+        if ((x & 1) && home(x) == c - 1) {
           bf16x2 pk;
-          pk[0] = (__bf16)sc[e / 16][0][(e - 1) % 16];
-          pk[1] = (__bf16)sc[e / 16][0][e % 16];
-          sum_even += sc[e / 16][0][(e - 1) % 16];
-          sum_odd += sc[e / 16][0][e % 16];
-          pf[e / 8][(e % 8) - 1] = pk[0];
-          pf[e / 8][e % 8] = pk[1];
+          pk[0] = (__bf16)sc[e / 16][rb][(e - 1) % 16];
+          pk[1] = (__bf16)sc[e / 16][rb][e % 16];
+          sum_even[rb] += sc[e / 16][rb][(e - 1) % 16];
+          sum_odd[rb] += sc[e / 16][rb][e % 16];
+          pf[ks][rb][e8 - 1] = pk[0];
+          pf[ks][rb][e8] = pk[1];
         }
       }
     };
@@ -516,22 +452,23 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
 #pragma unroll
     for (int i = 0; i < LA; ++i) fetch(i);
     __builtin_amdgcn_sched_barrier(0);
-    static_for<0, NQK + NPV>([&](auto ct_) __attribute__((always_inline)) {
+    static_for<0, NCH>([&](auto ct_) __attribute__((always_inline)) {
       constexpr int c = decltype(ct_)::value;
-      fetch(c + LA);
-      if constexpr (c < NQK) {
-        sn[c / KK][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], qf[0][c % KK],
-                                                                sn[c / KK][0], 0, 0, 0);
+      constexpr int f = c / RB, rb = c % RB;      // fragment and row block of this chunk's MFMA
+      if constexpr (rb == 0) fetch(f + LA);
+      if constexpr (f < NQK) {
+        sn[f / KK][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[f % (LA + 1)], qf[rb][f % KK],
+                                                                 sn[f / KK][rb], 0, 0, 0);
       } else {
-        constexpr int j = c - NQK;
-        oacc[j % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[c % (LA + 1)], pf[j / DB],
-                                                                  oacc[j % DB][0], 0, 0, 0);
+        constexpr int j = f - NQK;
+        pv_mfma<(RB > 1)>(oacc[j % DB][rb], frag[f % (LA + 1)], pf[j / DB][rb]);
       }
       softmax_slice(c);
       mid_copy(c);
-      if (c < NQK + NPV - DB) __builtin_amdgcn_sched_barrier(0);
+      if (c < NCH - DB * RB) __builtin_amdgcn_sched_barrier(0);
     });
-    l_run[0] += sum_even + sum_odd;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) l_run[rb] += sum_even[rb] + sum_odd[rb];
     if (decltype(mask_tag)::value) mask_tile(sn, next_key0);   // the next tile touches the diagonal
     raise_max(sn);
   };
@@ -650,6 +587,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     if (wave_live) tail_step(s_a, v_cur);
   }
   wait_pending(std::integral_constant<int, 0>{});   // let the unused trailing copies drain
+  if constexpr (RB > 1) mfma_drain();
 
   // ---- epilogue
 #pragma unroll
@@ -749,11 +687,10 @@ static int launch_attn_t(const LaunchParams &p, hipStream_t st) {
   static const hipError_t attr = hipFuncSetAttribute(
       (const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (attr != hipSuccess) return (int)attr;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)p.num_items), dim3(NW * 64), lds_bytes, st,
-                     (const __bf16 *)p.q, (const __bf16 *)p.k_pool, (const __bf16 *)p.v_pool,
-                     p.block_table, (__bf16 *)p.out, p.partials, p.items, p.Hq, p.Hkv, p.max_blocks,
-                     p.scale_log2e);
-  return (int)hipGetLastError();
+  return launch_kernel(kernel, dim3((unsigned)p.num_items), dim3(NW * 64), lds_bytes, st,
+                       (const __bf16 *)p.q, (const __bf16 *)p.k_pool, (const __bf16 *)p.v_pool,
+                       p.block_table, (__bf16 *)p.out, p.partials, p.items, p.Hq, p.Hkv, p.max_blocks,
+                       p.scale_log2e);
 }
 
 // Tile shapes: 64 and 128 query rows run two workgroups per CU with two-slot
@@ -763,6 +700,7 @@ static int launch_attn_t(const LaunchParams &p, hipStream_t st) {
 int launch_attention(const LaunchParams &p, void *stream) {
   if (p.num_items == 0) return 0;
   hipStream_t st = (hipStream_t)stream;
+  if (p.rows_per_wave == 64) return launch_attention64(p, stream);
   if (p.d == 128) {
     if (p.tile_rows == 64) return launch_attn_t<128, 1, 2, 2, 2>(p, st);
     if (p.tile_rows == 128) return launch_attn_t<128, 1, 4, 2, 2>(p, st);
@@ -778,14 +716,13 @@ int launch_reduce(const LaunchParams &p, void *stream) {
   hipStream_t st = (hipStream_t)stream;
   if (p.d == 128) {
     dim3 grid((unsigned)p.num_groups, (unsigned)((p.tile_rows + 7) / 8));
-    hipLaunchKernelGGL(split_reduce_kernel<128>, grid, dim3(256), 0, st, p.partials, (__bf16 *)p.out,
-                       p.groups, p.tile_rows, p.Hq, p.Hkv, p.scale_log2e);
+    return launch_kernel(split_reduce_kernel<128>, grid, dim3(256), 0, st, (const float *)p.partials,
+                         (__bf16 *)p.out, p.groups, p.tile_rows, p.Hq, p.Hkv, p.scale_log2e);
   } else {
     dim3 grid((unsigned)p.num_groups, (unsigned)((p.tile_rows + 15) / 16));
-    hipLaunchKernelGGL(split_reduce_kernel<64>, grid, dim3(256), 0, st, p.partials, (__bf16 *)p.out,
-                       p.groups, p.tile_rows, p.Hq, p.Hkv, p.scale_log2e);
+    return launch_kernel(split_reduce_kernel<64>, grid, dim3(256), 0, st, (const float *)p.partials,
+                         (__bf16 *)p.out, p.groups, p.tile_rows, p.Hq, p.Hkv, p.scale_log2e);
   }
-  return (int)hipGetLastError();
 }
 
 // --------------------------------------------------------------------------
@@ -827,15 +764,13 @@ __global__ __launch_bounds__(256) void read_peak_kernel(const u32x4 *__restrict_
 
 int launch_mfma_peak(float *sink, int iters, int *waves, void *stream) {
   const int blocks = 2 * kNumCU;
-  hipLaunchKernelGGL(mfma_peak_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
   *waves = blocks * 4;
-  return (int)hipGetLastError();
+  return launch_kernel(mfma_peak_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
 }
 
 int launch_read_peak(const void *src, size_t bytes, float *sink, void *stream) {
-  hipLaunchKernelGGL(read_peak_kernel, dim3(16 * kNumCU), dim3(256), 0, (hipStream_t)stream,
-                     (const u32x4 *)src, bytes / 16, sink);
-  return (int)hipGetLastError();
+  return launch_kernel(read_peak_kernel, dim3(16 * kNumCU), dim3(256), 0, (hipStream_t)stream,
+                       (const u32x4 *)src, bytes / 16, sink);
 }
 
 }  // namespace prism

@@ -47,6 +47,9 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
   if (rc != PRISM_OK) return rc;
   int tile_rows = opt.tile_rows ? opt.tile_rows : 128;
   if (tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return PRISM_ERR_UNSUPPORTED;
+  const int rows_per_wave = opt.rows_per_wave ? opt.rows_per_wave : 32;
+  if (rows_per_wave != 32 && rows_per_wave != 64) return PRISM_ERR_UNSUPPORTED;
+  if (rows_per_wave == 64 && tile_rows == 64) return PRISM_ERR_UNSUPPORTED;
   if (opt.split_kv < 0 || opt.min_split_keys < 0 || opt.min_split_keys % kTileKeys != 0)
     return PRISM_ERR_UNSUPPORTED;
   const int G = s.num_q_heads / s.num_kv_heads;
@@ -54,6 +57,7 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
 
   Schedule sch;
   sch.tile_rows = tile_rows;
+  sch.rows_per_wave = rows_per_wave;
   std::vector<int32_t> q_off(s.batch);
   int64_t total = 0;
   for (int r = 0; r < s.batch; ++r) {
@@ -61,6 +65,7 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
     if (P < 0 || S < 0) return PRISM_ERR_INVALID_ARG;
     if (P + S > (int64_t)kPage * s.max_blocks_per_req) return PRISM_ERR_INVALID_ARG;
     if (total + S > INT32_MAX / 2) return PRISM_ERR_INVALID_ARG;
+    if (S * s.num_kv_heads * (d / 8) > INT32_MAX / 2) return PRISM_ERR_INVALID_ARG;   // 16-byte units of one request
     q_off[r] = (int32_t)total;
     total += S;
     sch.flops += 4LL * d * s.num_q_heads * (S * P + S * (S + 1) / 2);
@@ -68,9 +73,7 @@ int build_schedule(const prism_shape_t &s, const int32_t *prefix, const int32_t 
   }
   sch.total_suffix = total;
 
-  sch.toks.reserve((size_t)total);
-  for (int r = 0; r < s.batch; ++r)
-    for (int i = 0; i < suffix[r]; ++i) sch.toks.push_back(TokInfo{r, prefix[r] + i});
+  sch.q_off = q_off;
 
   // Requests that share a cached prefix start with the same page: give them
   // one cluster id (the smallest request index of the cluster).

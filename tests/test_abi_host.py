@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(lib):
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["prism.h", "prism_sched.h"]
     for name in declared:
         assert hasattr(lib, name), name
-    assert B.prism_version() == 100
+    assert B.prism_version() == 200
     assert lib.prism_strerror(B.ERR_UNSUPPORTED).decode().startswith("unsupported")
 
 
@@ -106,7 +106,10 @@ def _check_cover(b, tile_rows, split_kv, min_split_keys=0):
             assert [c[2] for c in chunks] == list(range(chunks[0][2], chunks[0][2] + len(chunks)))
             nsplit_items += len(chunks)
     assert info.num_split_items == nsplit_items == len(slots)
-    assert ws == len(slots) * tr * (b.geom.head_dim + 2) * 4
+    # workspace: the work lists (64-byte items, 32-byte merge groups, each part
+    # padded to 256 bytes), then one fp32 partial slot per split item
+    up = lambda n: -(-n // 256) * 256
+    assert ws == up(64 * info.num_items) + up(32 * info.num_reduce_groups) + len(slots) * tr * (b.geom.head_dim + 2) * 4
     S64, P64 = b.suffix_len.astype(np.int64), b.prefix_len.astype(np.int64)
     assert info.flops == 4 * b.geom.head_dim * b.geom.num_q_heads * int((S64 * P64 + S64 * (S64 + 1) // 2).sum())
     assert info.total_suffix == b.total_suffix

@@ -21,22 +21,43 @@ def test_tiny_config_all_rows(oracle_lib):
     full_parity(oracle_lib, W.make_config(0))
 
 
-@pytest.mark.parametrize("tile_rows", [64, 128, 256])
+# (tile_rows, rows_per_wave): every kernel shape the planner can pick
+SHAPES = [(64, 32), (128, 32), (256, 32), (128, 64), (256, 64)]
+SHAPE_IDS = [f"{t}x{w}" for t, w in SHAPES]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=SHAPE_IDS)
 @pytest.mark.parametrize("geom", [W.Geometry(4, 4, 64), W.Geometry(8, 2, 128), W.Geometry(6, 6, 128),
                                    W.Geometry(8, 1, 64)], ids=["mha64", "gqa4x128", "mha128", "mqa8x64"])
-def test_ragged_lengths_all_rows(oracle_lib, geom, tile_rows):
+def test_ragged_lengths_all_rows(oracle_lib, geom, shape):
     """Prefixes and suffixes that end inside pages and tiles, an empty request,
     a request with no cached prefix, and a single-token one."""
     prefix = [0, 16, 37, 200, 64, 129, 0]
     suffix = [70, 0, 19, 33, 130, 65, 1]
     b = W.make_custom_batch("ragged", geom, prefix, suffix, seed=5, share_groups=[-1, 0, -1, 0, 0, -1, -1])
-    full_parity(oracle_lib, b, tile_rows=tile_rows)
+    full_parity(oracle_lib, b, tile_rows=shape[0], rows_per_wave=shape[1])
 
 
+@pytest.mark.parametrize("shape", SHAPES, ids=SHAPE_IDS)
+@pytest.mark.parametrize("geom", [W.Geometry(2, 2, 128), W.Geometry(8, 2, 128), W.Geometry(4, 4, 64)],
+                         ids=["mha128", "gqa4x128", "mha64"])
+def test_long_prefixes_run_the_steady_state_loop(oracle_lib, geom, shape):
+    """Cached prefixes of 1 000 to 2 600 tokens: dozens of unmasked key tiles
+    before the causal diagonal, so the unrolled steady-state loop of every
+    kernel shape (ring slots fixed in the code, copies interleaved with the
+    math) runs several trips, then hands over to the masked tail.  Ragged
+    suffixes leave some waves of a workgroup without rows."""
+    prefix = [1024, 2600, 1500, 1040]
+    suffix = [300, 40, 129, 64]
+    b = W.make_custom_batch("steady", geom, prefix, suffix, seed=15, share_groups=[0, -1, 0, -1])
+    full_parity(oracle_lib, b, tile_rows=shape[0], rows_per_wave=shape[1])
+
+
+@pytest.mark.parametrize("shape", [(128, 32), (128, 64), (256, 64)], ids=["128x32", "128x64", "256x64"])
 @pytest.mark.parametrize("split_kv", [2, 3, 7])
-def test_split_kv_matches_oracle(oracle_lib, split_kv):
+def test_split_kv_matches_oracle(oracle_lib, split_kv, shape):
     b = W.make_custom_batch("split", W.Geometry(8, 2, 128), [500, 0, 1000, 77], [40, 300, 7, 150], seed=6)
-    info = full_parity(oracle_lib, b, split_kv=split_kv)
+    info = full_parity(oracle_lib, b, split_kv=split_kv, tile_rows=shape[0], rows_per_wave=shape[1])
     assert info.num_reduce_groups > 0
 
 
@@ -53,8 +74,9 @@ def test_split_and_unsplit_agree():
     assert dmax <= 2.0 ** -7 * amax, (dmax, amax)
 
 
+@pytest.mark.parametrize("shape", [(128, 32), (128, 64), (256, 64)], ids=["128x32", "128x64", "256x64"])
 @pytest.mark.parametrize("scale,name", [(1.0, "unit"), (4.0, "sharp")])
-def test_unscaled_and_sharp_inputs(oracle_lib, scale, name):
+def test_unscaled_and_sharp_inputs(oracle_lib, scale, name, shape):
     """q,k,v ~ N(0,1) (logits of order 1, outputs of order 0.1-1, so the
     absolute tolerance bites) and q,k ~ 4 N(0,1) (logit std 16: the max
     subtraction matters)."""
@@ -64,10 +86,11 @@ def test_unscaled_and_sharp_inputs(oracle_lib, scale, name):
     def mutate(t):
         for k in ("q", "k_suffix", "k_pool"):
             t[k].mul_(scale)
-    full_parity(oracle_lib, b, mutate=mutate)
+    full_parity(oracle_lib, b, mutate=mutate, tile_rows=shape[0], rows_per_wave=shape[1])
 
 
-def test_slots_past_the_sequence_are_ignored(oracle_lib):
+@pytest.mark.parametrize("shape", [(128, 32), (128, 64), (256, 64)], ids=["128x32", "128x64", "256x64"])
+def test_slots_past_the_sequence_are_ignored(oracle_lib, shape):
     """The last page's unused slots (and unrelated pages) hold NaN/Inf bit
     patterns; results must not change."""
     geom = W.Geometry(4, 4, 128)
@@ -80,7 +103,7 @@ def test_slots_past_the_sequence_are_ignored(oracle_lib):
             if T % 16:
                 t["k_pool"][pg, :, T % 16:, :] = float("nan")
                 t["v_pool"][pg, :, T % 16:, :] = float("inf")
-    full_parity(oracle_lib, b, mutate=mutate)
+    full_parity(oracle_lib, b, mutate=mutate, tile_rows=shape[0], rows_per_wave=shape[1])
 
 
 def test_page_permutation_invariance():
@@ -260,7 +283,8 @@ def test_pages_beyond_the_4_gib_offset(oracle_lib):
     plan = B.Plan(shape, small.prefix_len, small.suffix_len, block_table=table)
     bt = torch.from_numpy(table).cuda()
     out = torch.full_like(t["q"], float("nan"))
-    plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], big["k_pool"], big["v_pool"], bt, out, None)
+    ws = torch.empty(plan.prism_plan_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], big["k_pool"], big["v_pool"], bt, out, ws)
     torch.cuda.synchronize()
     plan.close()
     host = {k: W.bf16_bits(v) for k, v in t.items()}
@@ -341,3 +365,77 @@ def test_prefill_call_replays_from_a_hip_graph():
         assert torch.equal(t["k_pool"].view(torch.int16), pools_eager[0].view(torch.int16))
         assert torch.equal(t["v_pool"].view(torch.int16), pools_eager[1].view(torch.int16))
     plan.close()
+
+
+def test_plan_lifetime_never_waits_for_the_device(oracle_lib):
+    """Creating, using and destroying a plan waits for no other stream: a long
+    run of GEMMs on a side stream is still going after a whole plan lifetime on
+    the main stream (the library allocates no device memory, copies its work
+    lists asynchronously on the caller's stream, and destroy waits for that
+    copy only - not for the kernels it enqueued, which need nothing of the
+    plan's any more)."""
+    b = W.make_custom_batch("nosync", W.Geometry(8, 2, 128), [300, 64], [70, 33], seed=41)
+    t = W.make_tensors(b, "cuda")
+    host = {k: W.bf16_bits(v) for k, v in t.items()}
+    bt = torch.from_numpy(b.block_table).cuda()
+    out = torch.full_like(t["q"], float("nan"))
+    # a first lifetime loads the kernels, so that the timed one below is short
+    warm = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, block_table=b.block_table, split_kv=2)
+    ws = torch.empty(warm.prism_plan_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    pools = (t["k_pool"].clone(), t["v_pool"].clone())
+    warm.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], pools[0], pools[1], bt, out, ws)
+    torch.cuda.synchronize()
+    warm.close()
+    side = torch.cuda.Stream()
+    done = torch.cuda.Event()
+    a = torch.randn(8192, 8192, device="cuda")
+    c = torch.empty_like(a)
+    torch.mm(a, a, out=c)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(40):                                  # a few hundred milliseconds of fp32 GEMMs
+            torch.mm(a, a, out=c)
+        done.record()
+    assert not done.query(), "the side work is too short for this test"
+    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, block_table=b.block_table, split_kv=2)
+    assert not done.query(), "prism_plan_create waited for the side stream"
+    plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], t["k_pool"], t["v_pool"], bt, out, ws)
+    assert not done.query(), "prism_prefix_prefill waited for the side stream"
+    plan.close()                                             # with its kernels possibly still queued
+    assert not done.query(), "prism_plan_destroy waited for the side stream"
+    torch.cuda.synchronize()
+    kp, vp = oracle_lib.kv_append(host["k_suffix"], host["v_suffix"], host["k_pool"], host["v_pool"],
+                                  b.block_table, b.prefix_len, b.suffix_len)
+    assert np.array_equal(W.bf16_bits(t["k_pool"]), kp) and np.array_equal(W.bf16_bits(t["v_pool"]), vp)
+    ref = oracle_lib.attention(host["q"], kp, vp, b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale)
+    check_close(widen(W.bf16_bits(out)), ref, "nosync")
+
+
+def test_work_lists_follow_the_workspace():
+    """The work lists live in the caller's workspace: alternating between two
+    workspaces, reusing one after it was overwritten (with
+    prism_plan_forget_workspace), and a workspace at an offset inside a larger
+    buffer all give the same bits."""
+    b = W.make_custom_batch("lists", W.Geometry(8, 2, 128), [700, 64, 130], [150, 80, 20], seed=42)
+    t = W.make_tensors(b, "cuda")
+    bt = torch.from_numpy(b.block_table).cuda()
+    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, block_table=b.block_table, split_kv=3)
+    n = plan.prism_plan_workspace_bytes()
+    big = torch.empty(2 * n + 4096, dtype=torch.uint8, device="cuda")
+    ws_a, ws_b = big[:n], big[(n + 255) // 256 * 256 + 256:][:n]
+    outs = []
+    for ws in (ws_a, ws_b, ws_a, ws_b):
+        o = torch.full_like(t["q"], float("nan"))
+        plan.prism_prefix_attention(t["q"], t["k_pool"], t["v_pool"], bt, o, ws)
+        outs.append(o)
+    torch.cuda.synchronize()
+    ws_b.fill_(0)                                            # the caller reuses the memory ...
+    plan.prism_plan_forget_workspace()                       # ... and says so
+    o = torch.full_like(t["q"], float("nan"))
+    plan.prism_prefix_attention(t["q"], t["k_pool"], t["v_pool"], bt, o, ws_b)
+    outs.append(o)
+    torch.cuda.synchronize()
+    plan.close()
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+    assert torch.isfinite(outs[0].float()).all()
