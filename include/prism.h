@@ -186,6 +186,25 @@ int prism_prefix_prefill(const prism_plan_t *plan, const void *q, const void *k_
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * For callers that cannot allocate device memory at the point of the call
+ * (code under HIP graph capture, serving loops with a frozen memory pool,
+ * harnesses that forbid allocation): prism_prefix_prefill without a workspace
+ * argument.  The work lists and the split-KV partial results go into a scratch
+ * array of PRISM_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (each GPU the library runs on holds one until the process ends); the
+ * call allocates nothing.  A plan whose prism_plan_workspace_bytes exceeds
+ * PRISM_STATIC_SCRATCH_BYTES is refused with PRISM_ERR_WORKSPACE_TOO_SMALL
+ * (prism_last_hip_error has the text).  Every call on a GPU shares that GPU's
+ * array: calls must be ordered on one stream (or otherwise not overlap), also
+ * across plans; the array keeps the last call's contents and nothing in it
+ * needs clearing between calls.  Results are those of prism_prefix_prefill.
+ */
+#define PRISM_STATIC_SCRATCH_BYTES (64u << 20)
+int prism_prefix_prefill_static(const prism_plan_t *plan, const void *q, const void *k_suffix,
+                                const void *v_suffix, void *k_pool, void *v_pool,
+                                const int32_t *block_table_dev, void *out, void *hip_stream);
+
+/*
  * Debug check of a HOST copy of the block table: page ids in range, no two
  * suffix positions map to one (page, slot), no suffix write lands in a page
  * that another request lists among its cached prefix blocks.

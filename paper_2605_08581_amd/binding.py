@@ -23,7 +23,7 @@ EXPORTS = (
     "prism_version", "prism_strerror", "prism_last_hip_error", "prism_plan_create",
     "prism_plan_dry_run", "prism_plan_workspace_bytes", "prism_plan_get_info", "prism_plan_forget_workspace",
     "prism_plan_destroy", "prism_kv_append",
-    "prism_prefix_attention", "prism_prefix_prefill", "prism_validate",
+    "prism_prefix_attention", "prism_prefix_prefill", "prism_prefix_prefill_static", "prism_validate",
     "prism_plan_profile_enable", "prism_plan_profile_read", "prism_measure_peaks",
 )
 
@@ -102,6 +102,8 @@ def load():
     lib.prism_prefix_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.prism_prefix_prefill.restype = ctypes.c_int
     lib.prism_prefix_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.prism_prefix_prefill_static.restype = ctypes.c_int
+    lib.prism_prefix_prefill_static.argtypes = [vp] * 9
     lib.prism_validate.restype = ctypes.c_int
     lib.prism_validate.argtypes = [ctypes.POINTER(Shape), vp, vp, vp]
     lib.prism_plan_profile_enable.restype = ctypes.c_int
@@ -240,7 +242,7 @@ class Plan:
         if q is not False:
             _check("q", q, "bf16", n * row_q)
             _check("out", out, "bf16", n * row_q)
-            _check("workspace", workspace, "u8", self.prism_plan_workspace_bytes())
+            _check("workspace", workspace, "u8", self.prism_plan_workspace_bytes(), optional=True)
         if k_suffix is not False:
             _check("k_suffix", k_suffix, "bf16", n * row_kv)
             _check("v_suffix", v_suffix, "bf16", n * row_kv)
@@ -276,6 +278,14 @@ class Plan:
                                             _ptr(out), _ptr(workspace), nbytes, _stream())
         if rc != PRISM_OK:
             raise PrismError(rc, "prism_prefix_prefill")
+
+    def prism_prefix_prefill_static(self, q, k_suffix, v_suffix, k_pool, v_pool, block_table, out):
+        self._check_call(q, k_suffix, v_suffix, k_pool, v_pool, block_table, out, None)
+        rc = self._lib.prism_prefix_prefill_static(self._h, _ptr(q), _ptr(k_suffix), _ptr(v_suffix),
+                                                   _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                                   _ptr(out), _stream())
+        if rc != PRISM_OK:
+            raise PrismError(rc, "prism_prefix_prefill_static")
 
     def prism_plan_profile_enable(self, on: bool):
         self._lib.prism_plan_profile_enable(self._h, int(on))

@@ -89,8 +89,22 @@ struct PinnedPool {
 };
 PinnedPool g_pinned;
 
-// Machine shape the planner's placement assumes, checked once per device.
+// ---- scratch for prism_prefix_prefill_static -------------------------------
+// Device memory that exists without any allocation call: one copy per GPU the
+// library's code object is loaded on.  `static_scratch` names the symbol, not
+// an address; host code only ever uses the per-device pointer that
+// hipGetSymbolAddress returns.
+__device__ __align__(256) unsigned char static_scratch[PRISM_STATIC_SCRATCH_BYTES];
+
 constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  std::mutex mu;
+  void *ptr[kMaxDevices] = {};
+  uint64_t resident_plan[kMaxDevices] = {};     // serial of the plan whose work lists are in the scratch
+};
+StaticScratch g_static;
+
+// Machine shape the planner's placement assumes, checked once per device.
 std::mutex g_dev_mu;
 int g_dev_ok[kMaxDevices] = {};                  // 0 unknown, 1 fine, -1 not the expected chip
 
@@ -419,6 +433,11 @@ void prism_plan_destroy(prism_plan_t *plan) {
   }
   for (auto e : plan->free_events) (void)hipEventDestroy(e);
   g_pinned.give_back(plan->host_lists, plan->host_pinned, plan->host_capacity);
+  {
+    std::lock_guard<std::mutex> lock(g_static.mu);
+    for (int d = 0; d < kMaxDevices; ++d)
+      if (g_static.resident_plan[d] == plan->serial) g_static.resident_plan[d] = 0;
+  }
   delete plan;
 }
 
@@ -460,6 +479,49 @@ int prism_prefix_prefill(const prism_plan_t *plan, const void *q, const void *k_
   rc = do_append(plan, k_suffix, v_suffix, k_pool, v_pool, block_table_dev, hip_stream);
   if (rc != PRISM_OK) return rc;
   return do_attention(plan, q, k_pool, v_pool, block_table_dev, out, (unsigned char *)workspace, hip_stream);
+}
+
+int prism_prefix_prefill_static(const prism_plan_t *plan, const void *q, const void *k_suffix,
+                                const void *v_suffix, void *k_pool, void *v_pool,
+                                const int32_t *block_table_dev, void *out, void *hip_stream) {
+  if (!plan || !k_pool || !v_pool || !block_table_dev) return PRISM_ERR_INVALID_ARG;
+  if (plan->sch.total_suffix > 0 && (!q || !out || !k_suffix || !v_suffix)) return PRISM_ERR_INVALID_ARG;
+  if (plan->total_bytes > (size_t)PRISM_STATIC_SCRATCH_BYTES)
+    return fail_with(PRISM_ERR_WORKSPACE_TOO_SMALL,
+                     "this plan needs more scratch than prism_prefix_prefill_static holds; "
+                     "use prism_prefix_prefill with a caller workspace");
+  if (plan->sch.total_suffix == 0) return PRISM_OK;
+  int rc = check_device();
+  if (rc != PRISM_OK) return rc;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  unsigned char *scratch = nullptr;
+  bool resident = false;
+  {
+    std::lock_guard<std::mutex> lock(g_static.mu);
+    if (!g_static.ptr[dev]) {
+      // once per device, with that device current: its own copy of the array
+      void *sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(static_scratch));
+      if (e != hipSuccess || !sym) return hip_fail(e, "hipGetSymbolAddress(static scratch)");
+      g_static.ptr[dev] = sym;
+    }
+    scratch = (unsigned char *)g_static.ptr[dev];
+    resident = g_static.resident_plan[dev] == plan->serial;
+    g_static.resident_plan[dev] = plan->serial;
+  }
+  if (!resident) {
+    rc = upload_lists(plan, scratch, hip_stream);
+    if (rc != PRISM_OK) {
+      std::lock_guard<std::mutex> lock(g_static.mu);
+      g_static.resident_plan[dev] = 0;
+      return rc;
+    }
+  }
+  rc = do_append(plan, k_suffix, v_suffix, k_pool, v_pool, block_table_dev, hip_stream);
+  if (rc != PRISM_OK) return rc;
+  return do_attention(plan, q, k_pool, v_pool, block_table_dev, out, scratch, hip_stream);
 }
 
 int prism_validate(const prism_shape_t *shape, const int32_t *prefix_len_host,
