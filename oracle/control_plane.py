@@ -1,5 +1,8 @@
 """Plain-Python reference of the host control plane.  TEST INFRASTRUCTURE ONLY:
-the product path never imports this module.
+the product path never imports this module.  Every function is pinned by cases
+worked by hand from the paper's definitions (tests/test_control_plane_reference.py
+for the eviction key, the protection set, the eviction order and hit lengths;
+tests/golden/qas_worked_example.txt for a scheduling round).
 
 It restates, with dictionaries and sorts and no shortcuts, one scheduling round
 of QAS (Sec. 3.2, Eq. 9-12, Alg. 1), the eviction order that Eq. 13 / Alg. 2

@@ -467,6 +467,11 @@ def test_dart_eviction_prefers_private_then_low_priority_then_protected():
     order = d.evicted_log()
     kinds = [(nodes[i]["kind"], nodes[i]["segment"]) for i in order]
     assert kinds == [(S.SPAN_PRIVATE, -1)] * 3 + [(S.SPAN_REUSABLE, 1), (S.SPAN_REUSABLE, 2), (S.SPAN_REUSABLE, 0)]
+    # the plain-Python reference, given the same nodes, reclaims them in the same order, and
+    # its protection set is the one anchor of segment 0
+    assert ref.eviction_order(list(nodes.values()), 10 ** 8, "dart", f=1) == order
+    prot = ref.protection_set(list(nodes.values()), 1)
+    assert [nodes[i]["segment"] for i in prot] == [0] and {i for i, n in nodes.items() if n["protected"]} == prot
     # private suffixes went in order of last access
     assert [nodes[i]["last"] for i in order[:3]] == sorted(nodes[i]["last"] for i in order[:3])
 
