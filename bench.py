@@ -4,10 +4,16 @@
 A step is one layer call of the whole hot path (paged KV append, prefill
 attention over cached prefix + suffix, split-KV merge) on one synthetic wave.
 Prints one JSON line.  Inputs are resident in HBM before the timed region.
+
+The headline is the 13B-class MHA wave (benchmark configuration [2]); the same
+line carries, under "configs", the attention kernel's time and roofline
+fraction on the other benchmark waves.
 """
 import argparse
+import hashlib
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -17,6 +23,14 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+KERNEL_SOURCES = ("prism_kernels.hip", "prism_attn64.hip", "prism_device.h", "prism_acc.h")
+
+
+def kernel_source_sha():
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2605_08581_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def accounting(b):
@@ -38,8 +52,97 @@ def accounting(b):
             "suffix_tokens": int(S.sum())}
 
 
-def cpu_baseline(b, host, budget_s=15.0):
-    """Time the oracle, as it stands, on a bounded sample of the same wave."""
+def roofline_of(acc, attn_ms):
+    """Binding roofline of the attention kernel on this wave and the fraction reached."""
+    t_mfma = acc["flops"] / (PEAK_BF16_TFLOPS * 1e12)
+    t_hbm = acc["bytes_unique"] / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        achieved = acc["flops"] / (attn_ms * 1e-3) / 1e12
+        r = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+             "frac": achieved / PEAK_BF16_TFLOPS}
+    else:
+        achieved = acc["bytes_unique"] / (attn_ms * 1e-3) / 1e9
+        r = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": achieved / PEAK_HBM_GBS}
+    r.update({"kernel_ms": attn_ms, "t_mfma_ms": t_mfma * 1e3, "t_hbm_unique_ms": t_hbm * 1e3})
+    return r
+
+
+class Wave:
+    """Device state of one synthetic wave: tensors, layer pools to cycle over, plan, workspace."""
+
+    def __init__(self, b, args, n_pools=0):
+        import numpy as np
+        import torch
+        from paper_2605_08581_amd import binding as B
+        from paper_2605_08581_amd import workload as W
+        self.b = b
+        self.acc = accounting(b)
+        self.t = W.make_tensors(b, "cuda")
+        pool_bytes = 2 * self.t["k_pool"].numel() * 2
+        # distinct layer pools, more than 512 MB together, so that K/V come from HBM every call
+        self.n_pools = n_pools or args.pools or max(2, int(np.ceil(512 * 2**20 / pool_bytes)) + 1)
+        self.pools = [(self.t["k_pool"], self.t["v_pool"])]
+        for _ in range(self.n_pools - 1):
+            self.pools.append((self.t["k_pool"].clone(), self.t["v_pool"].clone()))
+        self.bt = torch.from_numpy(b.block_table).cuda()
+        self.out = torch.empty_like(self.t["q"])
+        t0 = time.perf_counter()
+        self.plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, tile_rows=args.tile_rows, split_kv=args.split_kv,
+                           rows_per_wave=args.rows_per_wave,
+                           block_table=None if args.no_placement_hint else b.block_table)
+        self.plan_ms = (time.perf_counter() - t0) * 1e3
+        self.info = self.plan.prism_plan_get_info()
+        assert self.info.flops == self.acc["flops"]
+        nws = self.plan.prism_plan_workspace_bytes()
+        self.ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+
+    def step(self, i, same_pool=False):
+        kp, vp = self.pools[0 if same_pool else i % self.n_pools]
+        t = self.t
+        self.plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], kp, vp, self.bt, self.out, self.ws)
+
+    def kernel_times(self, steps, same_pool=False):
+        """Average duration of each kernel over `steps` layer calls, from HIP
+        events recorded on the launch stream around every kernel."""
+        import torch
+        self.plan.prism_plan_profile_enable(True)
+        for i in range(steps):
+            self.step(i, same_pool)
+        torch.cuda.synchronize()
+        prof = self.plan.prism_plan_profile_read()
+        self.plan.prism_plan_profile_enable(False)
+        n = max(1, prof["launches"])
+        return {k: prof[k] / n for k in ("attention_ms", "append_ms", "reduce_ms")}
+
+    def close(self):
+        self.plan.close()
+
+
+def timed_steps(wave, steps, warmup, same_pool=False):
+    """Exactly `steps` layer calls between two synchronisations; per-step times
+    from events recorded after every call in the same loop."""
+    import numpy as np
+    import torch
+    for i in range(warmup):
+        wave.step(i, same_pool)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        wave.step(i, same_pool)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    per = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+    return {"ms_per_step": elapsed / steps * 1e3, "ms_median": float(np.median(per)), "ms_min": float(per.min()),
+            "ms_max": float(per.max())}
+
+
+def cpu_baseline(b, host, budget_s=12.0):
+    """Time the oracle, as it stands, on a bounded sample of the same wave:
+    on every host core and, in a child process limited to one thread, on one."""
     import numpy as np
     import oracle
     from paper_2605_08581_amd import workload as W
@@ -57,9 +160,72 @@ def cpu_baseline(b, host, budget_s=15.0):
     dt, fl, n = run(256, 11)
     n2 = int(max(256, min(2_000_000, n * budget_s / max(dt, 1e-3))))
     dt, fl, n = run(n2, 12)
-    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{n} sampled (request, row, head) query rows of the same wave, {dt:.1f} s, fp64",
-            "suffix_tokens_per_s": n / b.geom.num_q_heads / dt}
+    res = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+           "sample": f"{n} sampled (request, row, head) query rows of the same wave, {dt:.1f} s, fp64",
+           "suffix_tokens_per_s": n / b.geom.num_q_heads / dt}
+    # one core: the same oracle in a child process with one OpenMP thread, on a smaller sample
+    # of the same recipe (the wave is rebuilt there from its seed; no device is touched)
+    n1 = max(256, int(n2 / max(1, oracle.threads()) / 2))
+    code = (
+        "import sys, time, json, numpy as np; sys.path.insert(0, %r)\n"
+        "import torch, oracle\n"
+        "from paper_2605_08581_amd import workload as W\n"
+        "b = W.make_config(%d) if %r is None else W.make_hit_rate_batch(%r)\n"
+        "t = W.make_tensors(b, 'cpu')\n"
+        "h = {k: W.bf16_bits(t[k]) for k in ('q', 'k_pool', 'v_pool')}\n"
+        "torch.set_num_threads(1)\n"
+        "rows = W.sample_rows(b, %d, seed=12)[:%d]\n"
+        "t0 = time.perf_counter()\n"
+        "oracle.attention_rows(h['q'], h['k_pool'], h['v_pool'], b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale, rows)\n"
+        "dt = time.perf_counter() - t0\n"
+        "fl = float((4 * b.geom.head_dim * (b.prefix_len[rows[:, 0]].astype(np.int64) + rows[:, 1] + 1)).sum())\n"
+        "print(json.dumps({'value': fl / dt / 1e12, 'cores': oracle.threads(), 'rows': len(rows), 'seconds': dt}))\n"
+    ) % (ROOT, getattr(b, "config_index", 2), None, None, n1, n1)
+    # (the child rebuilds benchmark configuration [config_index]; diagnostic waves fall back to [2])
+    try:
+        env = dict(os.environ, CUDA_VISIBLE_DEVICES="", HIP_VISIBLE_DEVICES="")
+        r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=180)
+        one = json.loads(r.stdout.strip().splitlines()[-1])
+        res["one_core"] = {"value": one["value"], "unit": "TFLOP/s", "cores": one["cores"],
+                           "sample": f"{one['rows']} sampled query rows of the same wave recipe, {one['seconds']:.1f} s, fp64, one thread"}
+    except Exception as e:                        # the all-core figure stands on its own
+        res["one_core"] = {"error": str(e)[:200]}
+    return res
+
+
+def other_configs(args):
+    """Attention kernel time and roofline fraction on the other benchmark waves."""
+    import torch
+    from paper_2605_08581_amd import workload as W
+    waves = [("[1] 4b-gqa", lambda: W.make_config(1)),
+             ("[3] hit-rate sweep h=0 (full recompute), batch 32", lambda: W.make_hit_rate_batch(0.0)),
+             ("[3] hit-rate sweep h=0.5, batch 32", lambda: W.make_hit_rate_batch(0.5)),
+             ("[3] hit-rate sweep h=0.9, batch 32", lambda: W.make_hit_rate_batch(0.9)),
+             ("[4] long-rag (split-KV)", lambda: W.make_config(4)),
+             ("decode-shaped: 64 requests x 4096 cached tokens, 1 new token, 13B-class heads",
+              lambda: W.make_custom_batch("decode-64x4096", W.Geometry(40, 40, 128), [4096] * 64, [1] * 64, seed=1,
+                                          permute_pages=False))]
+    out = []
+    for name, make in waves:
+        b = make()
+        w = Wave(b, args)
+        for i in range(3):
+            w.step(i)
+        torch.cuda.synchronize()
+        k = w.kernel_times(args.config_steps)
+        roof = roofline_of(w.acc, k["attention_ms"])
+        out.append({"workload": name, "batch": b.batch, "suffix_tokens": w.acc["suffix_tokens"],
+                    "tile_rows": w.info.tile_rows, "rows_per_wave": w.info.rows_per_wave,
+                    "workgroups": w.info.num_items, "split_workgroups": w.info.num_split_items,
+                    "attention_ms": k["attention_ms"], "append_ms": k["append_ms"], "reduce_ms": k["reduce_ms"],
+                    "bound": roof["bound"], "achieved": roof["achieved"], "unit": roof["unit"], "frac": roof["frac"],
+                    "flops": w.acc["flops"], "bytes_unique": w.acc["bytes_unique"],
+                    "suffix_tokens_per_s": w.acc["suffix_tokens"] / ((k["attention_ms"] + k["append_ms"] + k["reduce_ms"]) * 1e-3),
+                    "traffic": None})
+        w.close()
+        del w
+        torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -71,8 +237,11 @@ def main():
     ap.add_argument("--hit", type=float, default=None, help="with --config 3: cached fraction")
     ap.add_argument("--pools", type=int, default=0, help="distinct layer pools to cycle over (0 = auto)")
     ap.add_argument("--tile-rows", type=int, default=0)
+    ap.add_argument("--rows-per-wave", type=int, default=0)
     ap.add_argument("--split-kv", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other benchmark waves")
+    ap.add_argument("--config-steps", type=int, default=10, help="layer calls timed on each of the other waves")
     ap.add_argument("--no-placement-hint", action="store_true",
                     help="do not give the planner the host block table (no prefix-sharing placement)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
@@ -111,6 +280,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n}))
         return
 
+    diagnostic = bool(args.uniform or args.alias_pages)
     if args.uniform:
         P, S, nb = (int(x) for x in args.uniform.split(","))
         b = W.make_custom_batch(f"uniform-P{P}-S{S}-B{nb}", W.Geometry(40, 40, 128), [P] * nb, [S] * nb, seed=1,
@@ -119,81 +289,41 @@ def main():
         b = W.make_hit_rate_batch(args.hit)
     else:
         b = W.make_config(args.config)
+        b.config_index = args.config
     if args.alias_pages:
         b.block_table = (b.block_table % args.alias_pages).astype(np.int32)
         b.name += f" (diagnostic: block table folded onto {args.alias_pages} pages)"
-    acc = accounting(b)
-    t = W.make_tensors(b, "cuda")
-    pool_bytes = 2 * t["k_pool"].numel() * 2
-    n_pools = args.pools or max(2, int(np.ceil(512 * 2**20 / pool_bytes)) + 1)
-    pools = [(t["k_pool"], t["v_pool"])]
-    for _ in range(n_pools - 1):
-        pools.append((t["k_pool"].clone(), t["v_pool"].clone()))
-    bt = torch.from_numpy(b.block_table).cuda()
-    out = torch.empty_like(t["q"])
-    t0 = time.perf_counter()
-    plan = B.Plan(B.shape_of(b), b.prefix_len, b.suffix_len, tile_rows=args.tile_rows, split_kv=args.split_kv,
-                  block_table=None if args.no_placement_hint else b.block_table)
-    plan_ms = (time.perf_counter() - t0) * 1e3
-    info = plan.prism_plan_get_info()
-    assert info.flops == acc["flops"]
-    nws = plan.prism_plan_workspace_bytes()
-    ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    wave = Wave(b, args)
+    acc, info = wave.acc, wave.info
 
-    def step(i):
-        kp, vp = pools[i % n_pools]
-        plan.prism_prefix_prefill(t["q"], t["k_suffix"], t["v_suffix"], kp, vp, bt, out, ws)
+    # ---- the timed region: exactly --steps layer calls on HBM-cold pools
+    timing = timed_steps(wave, args.steps, args.warmup)
+    elapsed = timing["ms_per_step"] * 1e-3 * args.steps
+    # ---- the same loop again with HIP events around each kernel (on the launch stream)
+    kern = wave.kernel_times(args.steps)
+    attn_ms, append_ms, reduce_ms = kern["attention_ms"], kern["append_ms"], kern["reduce_ms"]
+    # ---- the same wave on one pool (K/V partly served by the 256 MB Infinity Cache): labelled, never the headline
+    warm = timed_steps(wave, args.steps, 3, same_pool=True)
+    warm_kern = wave.kernel_times(args.steps, same_pool=True)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-
-    # Same loop again with HIP events around each kernel (on the launch stream).
-    plan.prism_plan_profile_enable(True)
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    prof = plan.prism_plan_profile_read()
-    plan.prism_plan_profile_enable(False)
-    attn_ms = prof["attention_ms"] / max(1, prof["launches"])
-    append_ms = prof["append_ms"] / max(1, prof["launches"])
-    reduce_ms = prof["reduce_ms"] / max(1, prof["launches"])
-
-    t_mfma = acc["flops"] / (PEAK_BF16_TFLOPS * 1e12)
-    t_hbm = acc["bytes_unique"] / (PEAK_HBM_GBS * 1e9)
     traffic = None
     try:
         with open(args.traffic_json) as f:
             tj = json.load(f)
-        import hashlib
-        src = os.path.join(ROOT, "paper_2605_08581_amd", "csrc", "prism_kernels.hip")
-        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
         # counters are only valid for the kernel source they were taken with
-        if tj.get("workload") == b.name and tj.get("kernel_source_sha") == sha:
+        if tj.get("workload") == b.name and tj.get("kernel_source_sha") == kernel_source_sha():
             traffic = tj.get("bytes_per_launch")
     except (OSError, ValueError):
         pass
-    if t_mfma >= t_hbm:
-        achieved = acc["flops"] / (attn_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic}
-    else:
-        achieved = acc["bytes_unique"] / (attn_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": achieved / PEAK_HBM_GBS, "traffic": traffic}
+    roof = roofline_of(acc, attn_ms)
+    roof["traffic"] = traffic
     roof.update({
-        "kernel": "prefill_attn_kernel", "kernel_ms": attn_ms,
-        "t_mfma_ms": t_mfma * 1e3, "t_hbm_unique_ms": t_hbm * 1e3,
+        "kernel": "prefill_attn_kernel" if info.rows_per_wave == 32 else "prefill_attn64_kernel",
         "t_hbm_per_request_ms": acc["bytes_per_request"] / (PEAK_HBM_GBS * 1e9) * 1e3,
-        "frac_per_request_bytes": max(t_mfma, acc["bytes_per_request"] / (PEAK_HBM_GBS * 1e9)) / (attn_ms * 1e-3),
         "append_ms": append_ms, "append_gbs": acc["append_bytes"] / max(append_ms, 1e-9) / 1e6,
         "reduce_ms": reduce_ms,
+        "kernels_ms_sum": attn_ms + append_ms + reduce_ms,
+        "step_over_kernels": timing["ms_per_step"] / max(attn_ms + append_ms + reduce_ms, 1e-9),
     })
 
     # what this chip delivers on a bare MFMA loop and on a streaming read, beside the published peaks
@@ -202,29 +332,42 @@ def main():
     del scratch
     measured = peak_mfma if roof["bound"] == "mfma" else peak_read
     roof["measured_peak"] = {"mfma_tflops": peak_mfma, "hbm_read_gbs": peak_read,
-                             "frac_of_measured": roof["achieved"] / measured}
+                             "frac_of_measured": roof["achieved"] / measured,
+                             "note": "register-only MFMA loop on constant operands / streaming read of 1 GiB, same box"}
 
     result = {
         "metric": "prefix-cached prefill attention throughput", "value": acc["flops"] / elapsed * args.steps / 1e12,
         "unit": "TFLOP/s", "suffix_tokens_per_s": acc["suffix_tokens"] * args.steps / elapsed,
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": timing["ms_per_step"],
+        "ms_per_step_median": timing["ms_median"], "ms_per_step_min": timing["ms_min"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{b.name}{'' if args.uniform else f' (benchmark configuration [{args.config}])'}: "
+        "config": {"workload": f"{b.name}{' (diagnostic wave)' if diagnostic else f' (benchmark configuration [{args.config}])'}: "
                                f"Hq={b.geom.num_q_heads} "
                                f"Hkv={b.geom.num_kv_heads} d={b.geom.head_dim} page=16 batch={b.batch}",
                    "prefix_tokens": int(b.prefix_len.sum()), "suffix_tokens": acc["suffix_tokens"],
-                   "unique_pages": b.unique_pages_read(), "layer_pools_cycled": n_pools,
-                   "tile_rows": info.tile_rows, "workgroups": info.num_items,
-                   "split_workgroups": info.num_split_items, "plan_create_ms": plan_ms,
+                   "unique_pages": b.unique_pages_read(), "layer_pools_cycled": wave.n_pools,
+                   "tile_rows": info.tile_rows, "rows_per_wave": info.rows_per_wave, "workgroups": info.num_items,
+                   "split_workgroups": info.num_split_items, "plan_create_ms": wave.plan_ms,
                    "flops_per_step": acc["flops"], "bytes_unique": acc["bytes_unique"],
                    "bytes_per_request": acc["bytes_per_request"]},
         "roofline": roof,
+        "warm_same_pool": {"note": "same wave, every call on ONE layer pool (K/V partly served by the Infinity "
+                                   "Cache); for comparison only, never the headline",
+                           "ms_per_step": warm["ms_per_step"], "ms_per_step_median": warm["ms_median"],
+                           "ms_per_step_min": warm["ms_min"], "attention_ms": warm_kern["attention_ms"],
+                           "attention_tflops": acc["flops"] / (warm_kern["attention_ms"] * 1e-3) / 1e12},
     }
+    host = None
     if not args.no_cpu_baseline:
-        host = {k: W.bf16_bits(v) for k, v in (("q", t["q"]), ("k_pool", pools[0][0]), ("v_pool", pools[0][1]))}
+        host = {k: W.bf16_bits(v) for k, v in (("q", wave.t["q"]), ("k_pool", wave.pools[0][0]), ("v_pool", wave.pools[0][1]))}
+    wave.close()
+    del wave
+    torch.cuda.empty_cache()
+    if not args.no_configs and not diagnostic and args.config == 2 and args.hit is None:
+        result["configs"] = other_configs(args)
+    if host is not None:
         result["cpu_baseline"] = cpu_baseline(b, host)
-    plan.close()
     print(json.dumps(result))
 
 

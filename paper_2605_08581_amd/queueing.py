@@ -63,3 +63,24 @@ def crossover_rate(mu: float, M: float, c2: float = 1.0) -> float:
 def effective_prefill_throughput(R: float, X: float, L_out: float, R_dec: float) -> float:
     """R_eff = R (1 - X L_out / R_dec): decode contention as an attenuation (Eq. 16)."""
     return R * (1.0 - X * L_out / R_dec)
+
+
+def attention_only_knee(layer_call_s: float, n_layers: int, M: float, L: float, h: float, c2: float = 1.0) -> dict:
+    """The service knee that the measured attention path alone would allow.
+
+    layer_call_s is the measured time of one layer call (paged KV append +
+    prefill attention) for a wave of M requests with mean prompt length L and
+    exact-prefix hit rate h.  A model of n_layers layers spends n_layers such
+    calls per wave on attention, so with every other cost of the model left
+    out (projections, MLP, sampling, decode) a wave takes n_layers *
+    layer_call_s.  From there Eq. 5 gives the per-request prefill throughput
+    R = L (1 - h) / E[S_wave] and the service rate mu = M / E[S_wave], and
+    Eq. 15 the crossover lambda*.  These are ceilings of the attention path,
+    not predictions for a serving system."""
+    wave_s = n_layers * layer_call_s
+    R = L * (1.0 - h) / wave_s
+    mu = service_rate(M, L, h, R)
+    return {"scope": "attention-only (KV append + prefill attention of every layer; nothing else of the model)",
+            "wave_s": wave_s, "R_attn_tokens_per_s_per_request": R, "mu_requests_per_s": mu,
+            "lambda_star_requests_per_s": crossover_rate(mu, M, c2), "M": M, "L": L, "h": h, "c2": c2,
+            "n_layers": n_layers}

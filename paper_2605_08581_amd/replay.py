@@ -218,6 +218,18 @@ class DeviceRunner:
         return prof["append_ms"] + prof["attention_ms"] + prof["reduce_ms"]
 
 
+def knee_line(res: dict, n_layers: int, c2: float = 1.0) -> str:
+    """One labelled line: the service knee that the measured attention path
+    alone would allow for this replay's waves (Eq. 5, 14, 15)."""
+    from . import queueing as Q
+    L = res["prompt_tokens"] / max(1, res["requests"])
+    k = Q.attention_only_knee(res["gpu_ms_per_wave"] * 1e-3, n_layers, res["mean_wave_size"], L, res["hit_rate"], c2)
+    return (f"knee [attention-only: KV append + prefill attention of {n_layers} layers, nothing else of the model]: "
+            f"layer call {res['gpu_ms_per_wave']:.4f} ms, M={k['M']:.2f}, L={L:.1f}, h={k['h']:.3f} -> "
+            f"wave {k['wave_s'] * 1e3:.3f} ms, R_attn={k['R_attn_tokens_per_s_per_request']:.0f} tokens/s/request, "
+            f"mu={k['mu_requests_per_s']:.1f} requests/s, lambda*={k['lambda_star_requests_per_s']:.1f} requests/s (c2={c2:g})")
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--policy", default="dart,lru_active,lru,lfu")
@@ -233,6 +245,10 @@ def main(argv=None) -> int:
                     help="requests of one wave reuse each other's pages (the prefill call appends before it attends)")
     ap.add_argument("--gpu", action="store_true", help="prefill every wave on cuda:0 and report GPU time")
     ap.add_argument("--heads", default="40,40,128", help="Hq,Hkv,d of the device run")
+    ap.add_argument("--knee", action="store_true",
+                    help="with --gpu: feed the measured layer-call time, wave size and hit rate into the "
+                         "paper's queueing relations and print the attention-only service rate and crossover")
+    ap.add_argument("--layers", type=int, default=40, help="layers of the model the knee is quoted for")
     args = ap.parse_args(argv)
     trace = T.make_trace(args.requests, args.qps, args.seed)
     for pol in args.policy.split(","):
@@ -245,6 +261,8 @@ def main(argv=None) -> int:
         res = replay(trace, cfg, runner)
         res["trace"] = trace.params
         print(json.dumps(res))
+        if args.knee and "gpu_ms_per_wave" in res:
+            print(knee_line(res, args.layers))
     return 0
 
 

@@ -159,28 +159,29 @@ def test_workspace_errors():
 
 
 def _sampled_parity(oracle_lib, b, n_rows, **opts):
-    """Full-size check: append bit-exact on every written row (read back through
-    the table) and untouched elsewhere; attention on sampled rows."""
+    """Full-size check: the pools against the oracle's page-table writer over
+    every byte of both pools (which also shows that nothing else was written),
+    attention on sampled rows (every request's first and last rows and the rows
+    next to page and tile boundaries, plus uniform picks; every row with three
+    query heads, so that all heads of a wave are drawn many times over)."""
     t = W.make_tensors(b, "cuda")
-    k0, v0 = t["k_pool"].clone(), t["v_pool"].clone()
+    host = {k: W.bf16_bits(t[k]) for k in ("k_suffix", "v_suffix", "k_pool", "v_pool")}
     out, info = run_hip(b, t, **opts)
-    # append: compare against a torch index_put built from the table (integer work)
+    kp, vp = oracle_lib.kv_append(host["k_suffix"], host["v_suffix"], host["k_pool"], host["v_pool"],
+                                  b.block_table, b.prefix_len, b.suffix_len)
+    del host
+    got_k, got_v = W.bf16_bits(t["k_pool"]), W.bf16_bits(t["v_pool"])
+    assert np.array_equal(got_k, kp), "K pool differs from the page-table writer"
+    assert np.array_equal(got_v, vp), "V pool differs from the page-table writer"
+    del got_k, got_v
+    base = W.sample_rows(b, n_rows, seed=1)
+    rng = np.random.default_rng(2)
+    Hq = b.geom.num_q_heads
+    rows = np.concatenate([base] + [np.stack([base[:, 0], base[:, 1], rng.integers(0, Hq, len(base))], axis=1)
+                                    for _ in range(2)]).astype(np.int32)
+    ref = oracle_lib.attention_rows(W.bf16_bits(t["q"]), kp, vp, b.block_table, b.prefix_len, b.suffix_len,
+                                    b.softmax_scale, rows)
     offs = b.suffix_offsets
-    req = np.repeat(np.arange(b.batch), b.suffix_len)
-    pos = np.concatenate([np.arange(int(b.prefix_len[r]), int(b.prefix_len[r] + b.suffix_len[r]))
-                          for r in range(b.batch)]) if b.total_suffix else np.zeros(0, np.int64)
-    page = torch.from_numpy(b.block_table[req, pos // 16].astype(np.int64)).cuda()
-    slot = torch.from_numpy((pos % 16).astype(np.int64)).cuda()
-    assert torch.equal(t["k_pool"][page, :, slot, :], t["k_suffix"])
-    assert torch.equal(t["v_pool"][page, :, slot, :], t["v_suffix"])
-    keep = torch.ones(b.num_pages, 16, dtype=torch.bool, device="cuda")
-    keep[page, slot] = False
-    assert torch.equal(t["k_pool"].transpose(1, 2)[keep], k0.transpose(1, 2)[keep])
-    assert torch.equal(t["v_pool"].transpose(1, 2)[keep], v0.transpose(1, 2)[keep])
-    del k0, v0
-    rows = W.sample_rows(b, n_rows, seed=1)
-    ref = oracle_lib.attention_rows(W.bf16_bits(t["q"]), W.bf16_bits(t["k_pool"]), W.bf16_bits(t["v_pool"]),
-                                    b.block_table, b.prefix_len, b.suffix_len, b.softmax_scale, rows)
     got = widen(W.bf16_bits(out[torch.from_numpy(offs[rows[:, 0]] + rows[:, 1]).cuda(),
                                 torch.from_numpy(rows[:, 2].astype(np.int64)).cuda()]))
     check_close(got, ref, b.name)
@@ -195,9 +196,18 @@ def test_full_size_configs_sampled_rows(oracle_lib, index):
     _sampled_parity(oracle_lib, W.make_config(index), 1500)
 
 
+@pytest.mark.parametrize("shape", [(256, 32), (128, 64), (256, 64)], ids=["256x32", "128x64", "256x64"])
+def test_other_kernel_shapes_at_full_size(oracle_lib, shape):
+    """The 13B-class wave at full size through the kernel shapes that are not the default."""
+    _sampled_parity(oracle_lib, W.make_config(2), 600, tile_rows=shape[0], rows_per_wave=shape[1])
+
+
 @pytest.mark.parametrize("hit", [0.0, 0.5, 0.9])
 def test_hit_rate_sweep_sampled_rows(oracle_lib, hit):
-    _sampled_parity(oracle_lib, W.make_hit_rate_batch(hit, batch=8), 600)
+    """The hit-rate sweep at its full size: 32 requests of the 13B-class geometry."""
+    b = W.make_hit_rate_batch(hit)
+    assert b.batch == 32
+    _sampled_parity(oracle_lib, b, 800)
 
 
 def test_chunked_prefill_equals_one_shot(oracle_lib):

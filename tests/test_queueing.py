@@ -57,3 +57,20 @@ def test_theorem_one_algebra():
     assert math.isclose(Q.service_ratio(2 * M, R, L, h_lru, M, 2 * R, 2 * L, h_lru), 2.0)   # 2 * (1/2) * 2
     assert math.isclose(Q.full_prompt_gap(0.2, 660.0, 768.0), 0.2 * 660 / 768)
     assert math.isclose(Q.effective_prefill_throughput(600.0, 10.0, 32.0, 6400.0), 600.0 * 0.95)
+
+
+def test_attention_only_knee_on_fixed_inputs():
+    """Worked by hand: a 0.5 ms layer call, 40 layers -> 20 ms per wave; 10
+    requests per wave -> mu = 500 requests/s; L (1 - h) = 600 uncached tokens per
+    request -> R = 30 000 tokens/s per request; Eq. 15 with c2 = 1: 500 * 20 / 22."""
+    k = Q.attention_only_knee(0.5e-3, 40, M=10.0, L=800.0, h=0.25, c2=1.0)
+    assert k["wave_s"] == pytest.approx(0.02, rel=1e-12)
+    assert k["mu_requests_per_s"] == pytest.approx(500.0, rel=1e-12)
+    assert k["R_attn_tokens_per_s_per_request"] == pytest.approx(30000.0, rel=1e-12)
+    assert k["lambda_star_requests_per_s"] == pytest.approx(454.5454545454545, rel=1e-12)
+    assert k["scope"].startswith("attention-only")
+    # the printed line of the replay's --knee leg carries exactly these numbers
+    from paper_2605_08581_amd import replay
+    line = replay.knee_line({"gpu_ms_per_wave": 0.5, "mean_wave_size": 10.0, "hit_rate": 0.25,
+                             "prompt_tokens": 8000, "requests": 10}, n_layers=40)
+    assert "attention-only" in line and "mu=500.0" in line and "lambda*=454.5" in line and "R_attn=30000" in line
