@@ -241,6 +241,8 @@ def main():
     ap.add_argument("--split-kv", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other benchmark waves")
+    ap.add_argument("--no-warm-pass", action="store_true",
+                    help="skip the labelled same-pool pass (keeps a profiler's per-kernel averages to HBM-cold calls)")
     ap.add_argument("--config-steps", type=int, default=10, help="layer calls timed on each of the other waves")
     ap.add_argument("--no-placement-hint", action="store_true",
                     help="do not give the planner the host block table (no prefix-sharing placement)")
@@ -253,6 +255,9 @@ def main():
     ap.add_argument("--alias-pages", type=int, default=0, metavar="N",
                     help="diagnostic: fold the block table onto the first N pages so that K/V are served "
                          "from cache instead of HBM (outputs are meaningless; timing and counters only)")
+    ap.add_argument("--operands", default="random", choices=["random", "zero"],
+                    help="diagnostic: 'zero' fills q and the pools with zeros - the same instruction stream with "
+                         "no operand switching, to show how much of the clock the data values cost")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -280,7 +285,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n}))
         return
 
-    diagnostic = bool(args.uniform or args.alias_pages)
+    diagnostic = bool(args.uniform or args.alias_pages or args.operands != "random")
     if args.uniform:
         P, S, nb = (int(x) for x in args.uniform.split(","))
         b = W.make_custom_batch(f"uniform-P{P}-S{S}-B{nb}", W.Geometry(40, 40, 128), [P] * nb, [S] * nb, seed=1,
@@ -295,6 +300,12 @@ def main():
         b.name += f" (diagnostic: block table folded onto {args.alias_pages} pages)"
     wave = Wave(b, args)
     acc, info = wave.acc, wave.info
+    if args.operands == "zero":
+        b.name += " (diagnostic: all-zero q, K and V)"
+        wave.t["q"].zero_()
+        for kp, vp in wave.pools:
+            kp.zero_()
+            vp.zero_()
 
     # ---- the timed region: exactly --steps layer calls on HBM-cold pools
     timing = timed_steps(wave, args.steps, args.warmup)
@@ -303,8 +314,10 @@ def main():
     kern = wave.kernel_times(args.steps)
     attn_ms, append_ms, reduce_ms = kern["attention_ms"], kern["append_ms"], kern["reduce_ms"]
     # ---- the same wave on one pool (K/V partly served by the 256 MB Infinity Cache): labelled, never the headline
-    warm = timed_steps(wave, args.steps, 3, same_pool=True)
-    warm_kern = wave.kernel_times(args.steps, same_pool=True)
+    warm = warm_kern = None
+    if not args.no_warm_pass:
+        warm = timed_steps(wave, args.steps, 3, same_pool=True)
+        warm_kern = wave.kernel_times(args.steps, same_pool=True)
 
     traffic = None
     try:
@@ -327,13 +340,20 @@ def main():
     })
 
     # what this chip delivers on a bare MFMA loop and on a streaming read, beside the published peaks
+    # (the MFMA loop once on constant operands and once on random bf16 values like the wave's:
+    # the chip's power management clocks the two very differently)
     scratch = torch.empty(2**30, dtype=torch.uint8, device="cuda").fill_(1)
-    peak_mfma, peak_read = B.prism_measure_peaks(scratch, repeats=3)
+    peak_mfma_const, peak_read = B.prism_measure_peaks(scratch, repeats=3)
+    scratch[:16384].view(torch.bfloat16).copy_(torch.randn(8192, device="cuda") * b.value_scale)
+    peak_mfma_random, _ = B.prism_measure_peaks(scratch[:2**24], repeats=3)
     del scratch
-    measured = peak_mfma if roof["bound"] == "mfma" else peak_read
-    roof["measured_peak"] = {"mfma_tflops": peak_mfma, "hbm_read_gbs": peak_read,
+    measured = peak_mfma_random if roof["bound"] == "mfma" else peak_read
+    roof["measured_peak"] = {"mfma_tflops_constant_operands": peak_mfma_const,
+                             "mfma_tflops_random_operands": peak_mfma_random, "hbm_read_gbs": peak_read,
                              "frac_of_measured": roof["achieved"] / measured,
-                             "note": "register-only MFMA loop on constant operands / streaming read of 1 GiB, same box"}
+                             "note": "register-only MFMA loop (about 10 ms per launch) on constant and on random bf16 "
+                                     "operands / streaming read of 1 GiB, same box; the fraction is against the "
+                                     "random-operand figure (MFMA bound) or the read figure (HBM bound)"}
 
     result = {
         "metric": "prefix-cached prefill attention throughput", "value": acc["flops"] / elapsed * args.steps / 1e12,
@@ -352,12 +372,14 @@ def main():
                    "flops_per_step": acc["flops"], "bytes_unique": acc["bytes_unique"],
                    "bytes_per_request": acc["bytes_per_request"]},
         "roofline": roof,
-        "warm_same_pool": {"note": "same wave, every call on ONE layer pool (K/V partly served by the Infinity "
-                                   "Cache); for comparison only, never the headline",
-                           "ms_per_step": warm["ms_per_step"], "ms_per_step_median": warm["ms_median"],
-                           "ms_per_step_min": warm["ms_min"], "attention_ms": warm_kern["attention_ms"],
-                           "attention_tflops": acc["flops"] / (warm_kern["attention_ms"] * 1e-3) / 1e12},
     }
+    if warm is not None:
+        result["warm_same_pool"] = {
+            "note": "same wave, every call on ONE layer pool (K/V partly served by the Infinity Cache); "
+                    "for comparison only, never the headline",
+            "ms_per_step": warm["ms_per_step"], "ms_per_step_median": warm["ms_median"],
+            "ms_per_step_min": warm["ms_min"], "attention_ms": warm_kern["attention_ms"],
+            "attention_tflops": acc["flops"] / (warm_kern["attention_ms"] * 1e-3) / 1e12}
     host = None
     if not args.no_cpu_baseline:
         host = {k: W.bf16_bits(v) for k, v in (("q", wave.t["q"]), ("k_pool", wave.pools[0][0]), ("v_pool", wave.pools[0][1]))}

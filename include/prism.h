@@ -227,7 +227,9 @@ int prism_plan_profile_read(prism_plan_t *plan, double *append_ms, double *atten
 /*
  * Measurement aid, not part of the method: what this chip delivers on a
  * register-only loop of the same 32x32x16 bf16 MFMA the attention kernel uses
- * (dense TFLOP/s over all compute units) and on a streaming read of
+ * (dense TFLOP/s over all compute units; the operands are the first 8 KiB of
+ * scratch_dev read as bf16, so the caller chooses between constant and random
+ * values - the sustained rate depends on them) and on a streaming read of
  * scratch_dev (GB/s; give it at least 1 GiB so that caches cannot serve it),
  * each the best of `repeats` timed launches after one warm-up.  bench.py prints
  * these beside the published peaks.  scratch_dev is DEVICE memory owned by the

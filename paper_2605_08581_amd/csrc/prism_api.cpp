@@ -593,10 +593,10 @@ int prism_measure_peaks(void *scratch_dev, size_t scratch_bytes, int32_t repeats
   // the sink is only written under a condition that does not occur; it lives
   // in the caller's buffer so that nothing is allocated here
   float *sink = (float *)scratch_dev;
-  const int iters = 4096;
+  const int iters = 32768;                        // ~10 ms per launch: long enough for the clock to settle
   int waves = 0;
   double ms = 0;
-  timed([&]() { return launch_mfma_peak(sink, iters, &waves, st); }, &ms);
+  timed([&]() { return launch_mfma_peak(scratch_dev, sink, iters, &waves, st); }, &ms);
   if (rc == PRISM_OK) *mfma_tflops = (double)waves * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12;
   const size_t bytes = scratch_bytes & ~(size_t)15;
   timed([&]() { return launch_read_peak(scratch_dev, bytes, sink, st); }, &ms);

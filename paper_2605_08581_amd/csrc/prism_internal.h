@@ -107,7 +107,7 @@ int launch_append(const void *k_src, const void *v_src, void *k_pool, void *v_po
                   const int32_t *block_table, const AppendChunk &chunk, int max_suffix, int Hkv, int d,
                   int max_blocks, void *stream);
 
-int launch_mfma_peak(float *sink, int iters, int *waves, void *stream);
+int launch_mfma_peak(const void *src, float *sink, int iters, int *waves, void *stream);
 int launch_read_peak(const void *src, size_t bytes, float *sink, void *stream);
 
 }  // namespace prism

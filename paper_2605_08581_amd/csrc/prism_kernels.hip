@@ -174,11 +174,15 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[db][rb][r] = 0.f;
-  float m_run[RB], l_run[RB];
+  // m_run: running maximum (raw score units), l_run: running sum, bound: the
+  // raw score above which the maximum has to be raised before exponentiating
+  float m_run[RB], l_run[RB], bound[RB];
+  const float slack = kRescaleThreshold / scale_log2e;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     m_run[rb] = -1e30f;
     l_run[rb] = 0.f;
+    bound[rb] = -1e30f;
   }
 
   // ---- paged copy: wave w moves units w*UPW .. w*UPW+UPW-1 of a tile; a unit
@@ -279,8 +283,11 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
           if (key > limit[rb]) sx[kb][rb][r] = -INFINITY;
         }
   };
-  // Row maxima of a score tile; raise the running maximum (and rescale what
-  // has been accumulated) only when some row of the wave needs it.
+  // The lane's own maximum of a score tile against a precomputed bound (the
+  // running maximum plus the slack): no cross-lane traffic on the common path.
+  // Only when some score of the wave exceeds its bound do the two lanes of a
+  // row exchange maxima, raise the running maximum and rescale what has been
+  // accumulated.
   auto raise_max = [&](const f32x16 (&sx)[KB][RB]) {
     float mx[RB];
     bool grow = false;
@@ -291,14 +298,14 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx[rb] = fmaxf(mx[rb], sx[kb][rb][r]);
-      mx[rb] = max_across_halves(mx[rb]);
-      grow |= (mx[rb] - m_run[rb]) * scale_log2e > kRescaleThreshold;
+      grow |= mx[rb] > bound[rb];
     }
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {
       if constexpr (RB > 1) mfma_drain();
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
-        const float m_new = fmaxf(m_run[rb], mx[rb]);
+        const float m_new = fmaxf(m_run[rb], max_across_halves(mx[rb]));
+        bound[rb] = m_new + slack;
         const float alpha = fast_exp2((m_run[rb] - m_new) * scale_log2e);
         m_run[rb] = m_new;
         l_run[rb] *= alpha;
@@ -313,18 +320,12 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   // P^T fragment of k-step ks from the scores (exp2, row sums, bf16 rounding)
   auto p_frag = [&](const f32x16 (&sx)[KB][RB], int ks, int rb, float mc) -> bf16x8 {
     bf16x8 pf;
-    bf16x2 ones;
-    ones[0] = (__bf16)1.0f;
-    ones[1] = (__bf16)1.0f;
     float sum = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      bf16x2 pk;
-      pk[0] = (__bf16)fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e], scale_log2e, -mc));
-      pk[1] = (__bf16)fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e + 1], scale_log2e, -mc));
-      sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);   // sums the rounded values
-      pf[e] = pk[0];
-      pf[e + 1] = pk[1];
+    for (int e = 0; e < 8; ++e) {
+      const float p = fast_exp2(fmaf(sx[ks >> 1][rb][8 * (ks & 1) + e], scale_log2e, -mc));
+      sum += p;                                   // the fp32 exponentials, as in the overlapped step
+      pf[e] = (__bf16)p;
     }
     l_run[rb] += sum;
     return pf;
@@ -490,10 +491,26 @@ __global__ __launch_bounds__(NW * 64, WPE) void prefill_attn_kernel(
   };
   const bool wave_live = my_nt > 0;
   f32x16 s_a[KB][RB], s_b[KB][RB];
+  if (nt > 0) copy_rows(k_pool, 0, 0, pages_of(0));
+  if constexpr (NS > 2) {
+    // With rings deeper than two slots copies stay in flight across
+    // iterations.  The compiler cannot count them (they are inline assembly),
+    // so as long as it believes the Q rows loaded above may still be on their
+    // way it waits for every outstanding load at the first MFMA of each
+    // iteration.  Wait here, once, for Q and K of tile 0, and pass the Q
+    // registers through an empty statement so that it knows.
+    wait_pending(std::integral_constant<int, 0>{});
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) __asm__ volatile("" : "+v"(qf[rb][kk]));
+  }
   if (nt > 0) {
     PageIds pg = pages_of(0);
+    copy_rows(v_pool, 1, 0, pg);
+    pg = pages_of(1);
 #pragma unroll
-    for (int j = 0; j < NS - 1; ++j) {
+    for (int j = 1; j < NS - 1; ++j) {
       copy_rows(k_pool, 0, j, pg);
       copy_rows(v_pool, 1, j, pg);
       pg = pages_of(j + 1);
@@ -728,13 +745,11 @@ int launch_reduce(const LaunchParams &p, void *stream) {
 // --------------------------------------------------------------------------
 // Machine ceilings as this chip delivers them, for reporting beside the
 // published peaks: a register-only MFMA loop and a streaming read.
-__global__ __launch_bounds__(256, 2) void mfma_peak_kernel(float *sink, int iters) {
-  bf16x8 a, b;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    a[e] = (__bf16)(float)((threadIdx.x + e) & 7);
-    b[e] = (__bf16)(float)((threadIdx.x - e) & 3);
-  }
+__global__ __launch_bounds__(256, 2) void mfma_peak_kernel(const bf16x8 *__restrict__ src, float *sink, int iters) {
+  // operands come from the caller's buffer: what the matrix pipes sustain
+  // depends on the values (constant operands switch far fewer gates than
+  // random ones, and the chip's power management sets the clock accordingly)
+  const bf16x8 a = src[threadIdx.x], b = src[256 + threadIdx.x];
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -749,7 +764,7 @@ __global__ __launch_bounds__(256, 2) void mfma_peak_kernel(float *sink, int iter
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int q = 0; q < 16; ++q) r += acc[i][q];
-  if (r == -1.0f) sink[0] = r;                    // never true: keeps the loop alive
+  if (r == -1.0f && iters < 0) sink[0] = r;       // never true: keeps the loop alive
 }
 
 __global__ __launch_bounds__(256) void read_peak_kernel(const u32x4 *__restrict__ src, size_t n_vec, float *sink) {
@@ -762,10 +777,11 @@ __global__ __launch_bounds__(256) void read_peak_kernel(const u32x4 *__restrict_
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u && n_vec == 1) sink[0] = 1.f;   // practically never
 }
 
-int launch_mfma_peak(float *sink, int iters, int *waves, void *stream) {
+int launch_mfma_peak(const void *src, float *sink, int iters, int *waves, void *stream) {
   const int blocks = 2 * kNumCU;
   *waves = blocks * 4;
-  return launch_kernel(mfma_peak_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
+  return launch_kernel(mfma_peak_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const bf16x8 *)src, sink,
+                       iters);
 }
 
 int launch_read_peak(const void *src, size_t bytes, float *sink, void *stream) {
