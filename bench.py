@@ -119,14 +119,18 @@ class Wave:
         self.plan.close()
 
 
-def timed_steps(wave, steps, warmup, same_pool=False):
-    """Exactly `steps` layer calls between two synchronisations; per-step times
-    from events recorded after every call in the same loop."""
+def timed_steps(wave, steps, warmup, same_pool=False, per_kernel=True):
+    """Exactly `steps` layer calls between two synchronisations.  Per-step
+    times come from one event recorded after every call, per-kernel times from
+    the library's own HIP events around each kernel on the launch stream, all
+    in the same loop (events cost about a microsecond each)."""
     import numpy as np
     import torch
     for i in range(warmup):
         wave.step(i, same_pool)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    if per_kernel:
+        wave.plan.prism_plan_profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     marks[0].record()
@@ -136,8 +140,14 @@ def timed_steps(wave, steps, warmup, same_pool=False):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     per = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
-    return {"ms_per_step": elapsed / steps * 1e3, "ms_median": float(np.median(per)), "ms_min": float(per.min()),
-            "ms_max": float(per.max())}
+    out = {"ms_per_step": elapsed / steps * 1e3, "ms_median": float(np.median(per)), "ms_min": float(per.min()),
+           "ms_max": float(per.max())}
+    if per_kernel:
+        prof = wave.plan.prism_plan_profile_read()
+        wave.plan.prism_plan_profile_enable(False)
+        n = max(1, prof["launches"])
+        out.update({k: prof[k] / n for k in ("attention_ms", "append_ms", "reduce_ms")})
+    return out
 
 
 def cpu_baseline(b, host, budget_s=12.0):
@@ -312,17 +322,14 @@ def main():
     # ---- the timed region: exactly --steps layer calls on HBM-cold pools
     timing = timed_steps(wave, args.steps, args.warmup)
     elapsed = timing["ms_per_step"] * 1e-3 * args.steps
-    # ---- the same loop again with HIP events around each kernel (on the launch stream)
-    kern = wave.kernel_times(args.steps)
-    attn_ms, append_ms, reduce_ms = kern["attention_ms"], kern["append_ms"], kern["reduce_ms"]
+    attn_ms, append_ms, reduce_ms = timing["attention_ms"], timing["append_ms"], timing["reduce_ms"]
     # ---- the same wave on one pool (K/V partly served by the 256 MB Infinity Cache): labelled, never the headline
     # ---- a longer run of the same loop: the first dozens of calls after an idle period fall into the
     # power management's transient (fast, then throttled hard, then settling); reported beside the headline
     sustained = timed_steps(wave, args.sustained_steps, 0) if args.sustained_steps else None
-    warm = warm_kern = None
+    warm = None
     if not args.no_warm_pass:
         warm = timed_steps(wave, args.steps, 3, same_pool=True)
-        warm_kern = wave.kernel_times(args.steps, same_pool=True)
 
     traffic = None
     try:
@@ -367,14 +374,16 @@ def main():
                                        "headline passes (clock settled); for comparison, not the headline",
                                "steps": args.sustained_steps, "ms_per_step": sustained["ms_per_step"],
                                "ms_per_step_median": sustained["ms_median"], "ms_per_step_min": sustained["ms_min"],
-                               "tflops": acc["flops"] / (sustained["ms_per_step"] * 1e-3) / 1e12}
+                               "tflops": acc["flops"] / (sustained["ms_per_step"] * 1e-3) / 1e12,
+                               "attention_ms": sustained["attention_ms"],
+                               "attention_frac_of_peak": roofline_of(acc, sustained["attention_ms"])["frac"]}
     if warm is not None:
         result["warm_same_pool"] = {
             "note": "same wave, every call on ONE layer pool (K/V partly served by the Infinity Cache); "
                     "for comparison only, never the headline",
             "ms_per_step": warm["ms_per_step"], "ms_per_step_median": warm["ms_median"],
-            "ms_per_step_min": warm["ms_min"], "attention_ms": warm_kern["attention_ms"],
-            "attention_tflops": acc["flops"] / (warm_kern["attention_ms"] * 1e-3) / 1e12}
+            "ms_per_step_min": warm["ms_min"], "attention_ms": warm["attention_ms"],
+            "attention_tflops": acc["flops"] / (warm["attention_ms"] * 1e-3) / 1e12}
     host = None
     if not args.no_cpu_baseline:
         host = {k: W.bf16_bits(v) for k, v in (("q", wave.t["q"]), ("k_pool", wave.pools[0][0]), ("v_pool", wave.pools[0][1]))}
