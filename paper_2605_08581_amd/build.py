@@ -38,6 +38,17 @@ def _compile(src: str, verbose: bool) -> str:
     return obj
 
 
+def emit_assembly(src: str, out_dir: str) -> str:
+    """Device-side assembly of one kernel source, with the flags of the build
+    (for checks of what the compiler generated around the inline assembly)."""
+    out = os.path.join(out_dir, os.path.splitext(src)[0] + ".s")
+    cmd = [_hipcc()] + FLAGS + ["-x", "hip", "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc -S failed on {src}:\n{r.stderr}")
+    return out
+
+
 def build(verbose: bool = False) -> str:
     """Compile every source and link libprism.so; always recompiles."""
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:

@@ -63,6 +63,11 @@ __device__ __forceinline__ void copy16_to_lds(i32x4 rsrc, uint32_t lane_off, uin
 #pragma unroll
   for (int i = 0; i < 4; ++i) rsrc[i] = __builtin_amdgcn_readfirstlane(rsrc[i]);
   lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+  // M0 (the LDS destination) is written and consumed inside this one statement.
+  // The compiler rejects M0 in a clobber list (a reserved register), so the
+  // kernels that copy this way use nothing for which the compiler would set
+  // M0 itself (no LDS-DMA builtins, no indexed register moves, no messages);
+  // tests/test_kernel_assembly.py checks the generated code for that.
   __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %0, 0 offen lds"
                    :
                    : "s"(rsrc), "v"(lane_off), "s"(lds_base)
