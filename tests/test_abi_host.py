@@ -122,6 +122,25 @@ def test_planner_covers_every_pair_once(lib, index, tile_rows):
     _check_cover(W.make_config(index), tile_rows, 0)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_planner_random_waves(lib, seed):
+    """Seeded random waves (empty requests, no prefix, single tokens, long and
+    short mixes, every head grouping) under every tile shape and split policy:
+    each (request, kv head, row, key) is covered exactly once."""
+    rng = np.random.default_rng(1000 + seed)
+    hkv = int(rng.choice([1, 2, 4, 5, 8]))
+    geom = W.Geometry(hkv * int(rng.choice([1, 2, 3, 4, 8])), hkv, int(rng.choice([64, 128])))
+    n = int(rng.integers(1, 12))
+    prefix = [int(rng.choice([0, 16, 100, 1000, 5000])) * int(rng.integers(0, 3)) for _ in range(n)]
+    suffix = [int(rng.choice([0, 1, 2, 31, 32, 33, 127, 128, 129, 700])) for _ in range(n)]
+    if sum(suffix) == 0:
+        suffix[0] = 5
+    b = W.make_custom_batch("rnd", geom, prefix, suffix, seed=seed)
+    tile_rows = int(rng.choice([0, 64, 128, 256]))
+    split_kv = int(rng.choice([0, 1, 2, 9]))
+    _check_cover(b, tile_rows, split_kv, min_split_keys=int(rng.choice([0, 64, 512])))
+
+
 def test_planner_forced_and_disabled_split(lib):
     b = W.make_custom_batch("t", W.Geometry(8, 2, 128), [0, 100, 1000, 37], [5, 0, 300, 129], seed=1)
     assert _check_cover(b, 128, 1).num_split_items == 0

@@ -106,6 +106,27 @@ def test_slots_past_the_sequence_are_ignored(oracle_lib, shape):
     full_parity(oracle_lib, b, mutate=mutate, tile_rows=shape[0], rows_per_wave=shape[1])
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_small_waves(oracle_lib, seed):
+    """Seeded random waves: head grouping, head dim, lengths (empty requests,
+    no prefix, single tokens, lengths around the tile and page edges), page
+    sharing, kernel shape and split policy all drawn at random; every row
+    against the oracle, both pools against the page-table writer."""
+    rng = np.random.default_rng(7000 + seed)
+    hkv = int(rng.choice([1, 2, 3, 4]))
+    geom = W.Geometry(hkv * int(rng.choice([1, 2, 4, 5])), hkv, int(rng.choice([64, 128])))
+    n = int(rng.integers(1, 7))
+    prefix = [int(rng.choice([0, 16, 37, 64, 129, 500, 1300])) for _ in range(n)]
+    suffix = [int(rng.choice([0, 1, 2, 31, 33, 64, 65, 127, 130, 260])) for _ in range(n)]
+    if sum(suffix) == 0:
+        suffix[0] = 7
+    groups = [int(rng.choice([-1, 0, 1])) for _ in range(n)]
+    b = W.make_custom_batch("rnd", geom, prefix, suffix, seed=seed, share_groups=groups)
+    shape = SHAPES[int(rng.integers(0, len(SHAPES)))]
+    split_kv = int(rng.choice([0, 1, 3]))
+    full_parity(oracle_lib, b, seed=seed, tile_rows=shape[0], rows_per_wave=shape[1], split_kv=split_kv)
+
+
 def test_page_permutation_invariance():
     geom = W.Geometry(8, 2, 128)
     b = W.make_custom_batch("perm", geom, [128, 64], [50, 90], seed=10, permute_pages=False)
